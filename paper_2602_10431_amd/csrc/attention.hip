@@ -1,0 +1,429 @@
+// Attention restricted to executed tokens.
+//
+// A bypassed token produces no query, key or value at a layer (the whole layer is skipped for it, Eq. 3),
+// so an executed token attends causally to the executed tokens of its own sequence only, in original
+// order, preceded by that layer's cache entries (which also hold executed tokens only).  Rows of the
+// compact q|k|v buffer are in ascending token order, so the executed tokens of sequence b are the rows
+// cu_exec[b] .. cu_exec[b+1]-1 and "causal" means "row index <= own row index".
+//
+// Two kernels:
+//   * flash_prefill: matrix-core tiles.  A workgroup of 4 waves owns 128 query rows of one (sequence,
+//     head); keys/values stream through LDS in tiles of 64.  S^T = K Q^T is computed so that a lane owns
+//     one query column (softmax statistics are per lane), and the probabilities, still in the MFMA
+//     accumulator layout, are fed straight back as the B operand of O^T = V^T P^T; V is transposed on
+//     its way into LDS.
+//   * decode: one workgroup per (executed row, kv head); lanes stream K and V rows with 16-byte loads,
+//     16 (or 8) lanes per key, online softmax per lane group, merged at the end.  Bandwidth-bound.
+#include "qtale_dev.h"
+#include "qtale_kernels.h"
+
+namespace qtale {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1.0e30f;
+
+struct AttnDev {
+    const half_t* qkv;
+    half_t* out;
+    int nh, nkv, width;          // width = (nh + 2 nkv) * d
+    const int32_t* count;
+    const int32_t* cu_exec;
+    const int32_t* row_seq;
+    const int2* items;           // prefill work list: (sequence, query tile)
+    const int32_t* n_items;
+    const half_t* k_cache;
+    const half_t* v_cache;
+    const int32_t* kv_old;
+    int cap;
+    float scale_log2;            // log2(e) / sqrt(d)
+};
+
+template <int D>
+__global__ void __launch_bounds__(256)
+flash_prefill_kernel(AttnDev p) {
+    constexpr int KS = D / 16;          // k-steps of the QK^T product
+    constexpr int DF = D / 32;          // 32-wide fragments of the head dimension
+    constexpr int KSTR = D + 8;         // LDS row stride of the K tile (halves)
+    constexpr int VSTR = 64 + 4;        // LDS row stride of the transposed V tile (halves)
+    constexpr int CH = (64 * D / 8) / 256;   // 16-byte chunks per thread per tile
+    __shared__ __attribute__((aligned(16))) half_t Ks[64 * KSTR];
+    __shared__ __attribute__((aligned(16))) half_t Vt[D * VSTR];
+
+    const int item = blockIdx.x;
+    if (item >= *p.n_items) return;
+    const int b = p.items[item].x, qt = p.items[item].y;
+    const int h = blockIdx.y;
+    const int hk = h / (p.nh / p.nkv);
+    const int row_begin = p.cu_exec[b];
+    const int n_b = p.cu_exec[b + 1] - row_begin;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // key/value source: the layer cache (new rows were appended before this kernel) or the compact buffer
+    const half_t* kbase;
+    const half_t* vbase;
+    int kv_stride, base_len;
+    if (p.k_cache) {
+        base_len = p.kv_old[b];
+        kv_stride = p.nkv * D;
+        kbase = p.k_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+        vbase = p.v_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+    } else {
+        base_len = 0;
+        kv_stride = p.width;
+        kbase = p.qkv + static_cast<size_t>(row_begin) * p.width + (p.nh + hk) * D;
+        vbase = kbase + p.nkv * D;
+    }
+    const int q_lo = qt * 128;                                   // first local query index of the block
+    const int q_cnt = min(128, n_b - q_lo);
+    int n_keys = base_len + q_lo + q_cnt;                        // keys visible to the last query
+    if (p.k_cache) n_keys = min(n_keys, p.cap);
+    const int n_tiles = (n_keys + 63) / 64;
+
+    // this lane's query (column of S^T): local index inside the sequence, clamped to a valid row
+    const int q_local = q_lo + min(wave * 32 + l32, q_cnt - 1);
+    const int limit = base_len + q_local + 1;                    // keys [0, limit) are visible
+    const int wave_limit = base_len + q_lo + min(wave * 32 + 31, q_cnt - 1) + 1;
+    const half_t* qrow = p.qkv + static_cast<size_t>(row_begin + q_local) * p.width + h * D;
+    half8_t qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * lhi);
+
+    float16_t o[DF];
+#pragma unroll
+    for (int df = 0; df < DF; ++df)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[df][r] = 0.0f;
+    float m_run = kNegBig, l_run = 0.0f;
+
+    // global -> register staging of one K/V tile: chunk c is key c / (D/8), 8 halves at (c % (D/8))*8.
+    // V is transposed on its way into LDS (Vt[column][key]).
+    U4 kreg[CH], vreg[CH];
+    auto fetch = [&](int tile) {
+        const int key0 = tile * 64;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = i * 256 + tid;
+            const int key = min(key0 + c / (D / 8), n_keys - 1);
+            kreg[i] = *reinterpret_cast<const U4*>(kbase + static_cast<size_t>(key) * kv_stride + (c % (D / 8)) * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = i * 256 + tid;
+            const int key = min(key0 + c / (D / 8), n_keys - 1);
+            vreg[i] = *reinterpret_cast<const U4*>(vbase + static_cast<size_t>(key) * kv_stride + (c % (D / 8)) * 8);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = i * 256 + tid;
+            *reinterpret_cast<U4*>(&Ks[(c / (D / 8)) * KSTR + (c % (D / 8)) * 8]) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = i * 256 + tid;
+            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8;
+            const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                reinterpret_cast<uint16_t*>(Vt)[(d0 + 2 * e) * VSTR + key] = static_cast<uint16_t>(w[e] & 0xffffu);
+                reinterpret_cast<uint16_t*>(Vt)[(d0 + 2 * e + 1) * VSTR + key] = static_cast<uint16_t>(w[e] >> 16);
+            }
+        }
+    };
+
+    fetch(0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        stage();
+        __syncthreads();
+        if (tile + 1 < n_tiles) fetch(tile + 1);
+        const int key0 = tile * 64;
+        if (key0 < wave_limit) {
+            // S^T = K Q^T : rows = keys (two 32-key fragments), column = this lane's query
+            float16_t st[2];
+#pragma unroll
+            for (int kf = 0; kf < 2; ++kf) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st[kf][r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    const half8_t ka = *reinterpret_cast<const half8_t*>(&Ks[(kf * 32 + l32) * KSTR + 16 * s + 8 * lhi]);
+                    st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qf[s], st[kf], 0, 0, 0);
+                }
+            }
+            // online softmax over the 32 scores this lane holds (the lane 32 away holds the other 32)
+            float mx = kNegBig;
+#pragma unroll
+            for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + kf * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+                    const float s = key < limit ? st[kf][r] * p.scale_log2 : kNegBig;
+                    st[kf][r] = s;
+                    mx = fmaxf(mx, s);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = exp2f(m_run - m_new);
+            m_run = m_new;
+            float psum = 0.0f;
+            half8_t pf[4];
+#pragma unroll
+            for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pv = exp2f(st[kf][r] - m_new);
+                    psum += pv;
+                    pf[kf * 2 + (r >> 3)][r & 7] = static_cast<half_t>(pv);
+                }
+            l_run = l_run * alpha + psum;
+#pragma unroll
+            for (int df = 0; df < DF; ++df)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[df][r] *= alpha;
+            // O^T += V^T P^T : k-step s2 covers keys 16 s2 .. 16 s2 + 15 of the tile; operand element e of a
+            // lane is key 16 s2 + 8 (e/4) + 4 (lane/32) + e%4, the order the accumulator layout produced
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) {
+#pragma unroll
+                for (int df = 0; df < DF; ++df) {
+                    const half_t* vrow = &Vt[(df * 32 + l32) * VSTR + 16 * s2 + 4 * lhi];
+                    const half4_t v0 = *reinterpret_cast<const half4_t*>(vrow);
+                    const half4_t v1 = *reinterpret_cast<const half4_t*>(vrow + 8);
+                    half8_t va;
+                    va[0] = v0[0]; va[1] = v0[1]; va[2] = v0[2]; va[3] = v0[3];
+                    va[4] = v1[0]; va[5] = v1[1]; va[6] = v1[2]; va[7] = v1[3];
+                    o[df] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pf[s2], o[df], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    if (wave * 32 + l32 < q_cnt) {
+        half_t* orow = p.out + static_cast<size_t>(row_begin + q_local) * (p.nh * D) + h * D;
+#pragma unroll
+        for (int df = 0; df < DF; ++df)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                half4_t v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = static_cast<half_t>(o[df][4 * g + e] * inv);
+                *reinterpret_cast<half4_t*>(orow + df * 32 + 8 * g + 4 * lhi) = v;
+            }
+    }
+}
+
+// Builds the prefill work list: one item per (sequence, tile of kAttnBQ executed rows).
+__global__ void __launch_bounds__(256)
+attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int2* __restrict__ items, int32_t* __restrict__ n_items) {
+    __shared__ int s_wave[4];
+    __shared__ int s_base;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_base = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < B; b0 += 256) {
+        const int b = b0 + threadIdx.x;
+        const int nt = b < B ? (cu_exec[b + 1] - cu_exec[b] + kAttnBQ - 1) / kAttnBQ : 0;
+        int incl = nt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int start = s_base + incl - nt;
+        for (int w = 0; w < wave; ++w) start += s_wave[w];
+        for (int q = 0; q < nt; ++q) items[start + q] = make_int2(b, nt - 1 - q);   // longest tiles first
+        __syncthreads();
+        if (threadIdx.x == 0) s_base += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *n_items = s_base;
+}
+
+// Decode-style attention: workgroup = (executed row, kv head); REP query heads share the kv head.
+template <int D, int REP>
+__global__ void __launch_bounds__(256)
+attn_decode_kernel(AttnDev p) {
+    constexpr int LPK = D / 8;            // lanes per key (each lane owns 8 of the D columns)
+    constexpr int KPW = 64 / LPK;         // keys per wave per step
+    constexpr int UNR = 4;
+    const int i = blockIdx.x;
+    if (i >= *p.count) return;
+    const int hk = blockIdx.y;
+    const int b = p.row_seq[i];
+    const int row_begin = p.cu_exec[b];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane % LPK, slot = lane / LPK;
+
+    const half_t* kbase;
+    const half_t* vbase;
+    int kv_stride, n_keys;
+    if (p.k_cache) {
+        kv_stride = p.nkv * D;
+        kbase = p.k_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+        vbase = p.v_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+        n_keys = min(p.kv_old[b] + (i - row_begin) + 1, p.cap);
+    } else {
+        kv_stride = p.width;
+        kbase = p.qkv + static_cast<size_t>(row_begin) * p.width + (p.nh + hk) * D;
+        vbase = kbase + p.nkv * D;
+        n_keys = i - row_begin + 1;
+    }
+
+    float q[REP][8];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        const half8_t qv = *reinterpret_cast<const half8_t*>(p.qkv + static_cast<size_t>(i) * p.width + (hk * REP + r) * D + sub * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[r][e] = static_cast<float>(qv[e]) * p.scale_log2;
+    }
+    float m_run[REP], l_run[REP], o[REP][8];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        m_run[r] = kNegBig;
+        l_run[r] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[r][e] = 0.0f;
+    }
+
+    const int step = 4 * KPW;             // keys per workgroup step
+    for (int kb = 0; kb < n_keys; kb += UNR * step) {          // trip count is uniform over the workgroup
+        const int k0 = kb + wave * KPW + slot;
+        half8_t kv[UNR], vv[UNR];
+        bool ok[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int key = k0 + u * step;
+            ok[u] = key < n_keys;
+            const int kc = ok[u] ? key : n_keys - 1;
+            kv[u] = *reinterpret_cast<const half8_t*>(kbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
+            vv[u] = *reinterpret_cast<const half8_t*>(vbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
+        }
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            float s[UNR];
+            float mx = m_run[r];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc = fmaf(q[r][e], static_cast<float>(kv[u][e]), acc);
+#pragma unroll
+                for (int off = LPK >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                s[u] = ok[u] ? acc : kNegBig;
+                mx = fmaxf(mx, s[u]);
+            }
+            const float alpha = exp2f(m_run[r] - mx);
+            m_run[r] = mx;
+            float lsum = l_run[r] * alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[r][e] *= alpha;
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const float pv = ok[u] ? exp2f(s[u] - mx) : 0.0f;
+                lsum += pv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[r][e] = fmaf(pv, static_cast<float>(vv[u][e]), o[r][e]);
+            }
+            l_run[r] = lsum;
+        }
+    }
+
+    // merge the key slots of a wave (lanes that own the same columns), then the four waves through LDS
+    __shared__ float sm[4][REP][D + 2];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+#pragma unroll
+        for (int off = LPK; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(m_run[r], off, 64);
+            const float l2 = __shfl_xor(l_run[r], off, 64);
+            const float mn = fmaxf(m_run[r], m2);
+            const float a1 = exp2f(m_run[r] - mn), a2 = exp2f(m2 - mn);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float o2 = __shfl_xor(o[r][e], off, 64);
+                o[r][e] = o[r][e] * a1 + o2 * a2;
+            }
+            l_run[r] = l_run[r] * a1 + l2 * a2;
+            m_run[r] = mn;
+        }
+        if (slot == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm[wave][r][sub * 8 + e] = o[r][e];
+            if (sub == 0) { sm[wave][r][D] = m_run[r]; sm[wave][r][D + 1] = l_run[r]; }
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < REP * D; c += 256) {
+        const int r = c / D, e = c % D;
+        float mn = kNegBig;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm[w][r][D]);
+        float num = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a = exp2f(sm[w][r][D] - mn);
+            num += sm[w][r][e] * a;
+            den += sm[w][r][D + 1] * a;
+        }
+        p.out[static_cast<size_t>(i) * (p.nh * D) + (hk * REP + r) * D + e] = static_cast<half_t>(num / den);
+    }
+}
+
+template <int D>
+static hipError_t launch_decode_d(const AttnDev& d, int rep, int rows, int nkv, hipStream_t stream) {
+    const dim3 grid(rows, nkv), block(256);
+    switch (rep) {
+        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, block, 0, stream, d); break;
+        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, block, 0, stream, d); break;
+        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4>), grid, block, 0, stream, d); break;
+        case 8: hipLaunchKernelGGL((attn_decode_kernel<D, 8>), grid, block, 0, stream, d); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
+    if (a.max_rows == 0) return hipSuccess;
+    AttnDev d{};
+    d.qkv = reinterpret_cast<const half_t*>(a.qkv);
+    d.out = reinterpret_cast<half_t*>(a.out);
+    d.nh = a.nh;
+    d.nkv = a.nkv;
+    d.width = (a.nh + 2 * a.nkv) * a.d;
+    d.count = a.count;
+    d.cu_exec = a.cu_exec;
+    d.row_seq = a.row_seq;
+    d.items = reinterpret_cast<const int2*>(a.items);
+    d.n_items = a.n_items;
+    d.k_cache = reinterpret_cast<const half_t*>(a.k_cache);
+    d.v_cache = reinterpret_cast<const half_t*>(a.v_cache);
+    d.kv_old = a.kv_old;
+    d.cap = a.cap;
+    d.scale_log2 = kLog2e / sqrtf(static_cast<float>(a.d));
+    const int rep = a.nh / a.nkv;
+    const bool decode_style = a.k_cache != nullptr && a.T <= 4 * a.B && (rep == 1 || rep == 2 || rep == 4 || rep == 8);
+    if (decode_style) {
+        return a.d == 128 ? launch_decode_d<128>(d, rep, a.max_rows, a.nkv, stream)
+                          : launch_decode_d<64>(d, rep, a.max_rows, a.nkv, stream);
+    }
+    hipLaunchKernelGGL(attn_items_kernel, dim3(1), dim3(256), 0, stream, a.cu_exec, a.B,
+                       reinterpret_cast<int2*>(a.items), a.n_items);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int items_max = (a.max_rows + kAttnBQ - 1) / kAttnBQ + a.B;
+    const dim3 grid(items_max, a.nh), block(256);
+    if (a.d == 128)
+        hipLaunchKernelGGL(flash_prefill_kernel<128>, grid, block, 0, stream, d);
+    else
+        hipLaunchKernelGGL(flash_prefill_kernel<64>, grid, block, 0, stream, d);
+    return hipGetLastError();
+}
+
+}  // namespace qtale

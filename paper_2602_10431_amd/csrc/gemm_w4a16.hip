@@ -1,0 +1,317 @@
+// W4A16 GEMM for the layer's linears on the compacted tokens: C[M][N] = A[M][K] (fp16) x W'[N][K]^T,
+// W' = (code - zero) * scale per group of the input dimension (Sec. 4.1 weight-only group quantization).
+//
+// Design for gfx950 (64-wide waves, v_mfma_f32_32x32x16_f16, 160 KB LDS):
+//   * Weights are the B operand.  In the prepacked layout one 16-byte load gives a lane the 4 x 8 codes
+//     of its row n = lane%32 for the four 16-wide k-steps of a 64-wide k-tile, already in operand order,
+//     so weights go HBM/L2 -> VGPR -> (dequantize) -> MFMA and never touch LDS.
+//   * Dequantisation is packed fp16: OR-ing a nibble into 0x6400 gives the fp16 value 1024 + c (low
+//     nibble position) or 1024 + 16 c (next position); (1024+c) - (1024+z) and (1024+16c)/16 - (64+z)
+//     are exact, one multiply by the scale rounds once.  13 VALU ops per 8 weights.
+//   * Activations are the A operand, staged global -> VGPR -> LDS (row stride 72 halves: conflict-free
+//     16-byte reads), double buffered, one barrier per k-tile; the next tile's global loads are issued
+//     before the current tile's MFMAs.
+//   * Epilogues fuse what follows the linear: fp16 store (q|k|v), residual add from the gathered rows
+//     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
+#include "qtale_dev.h"
+#include "qtale_kernels.h"
+
+namespace qtale {
+
+struct GemmDev {
+    const half_t* A;
+    const int32_t* count;
+    int M_max, K, KT, gshift;
+    const U4* codes[3];
+    const uint32_t* sz[3];
+    int N[3], NF[3], npad[3], colbase[3];
+    int n_w, vf_total, tiles_m, tiles_n;
+    void* out;
+    int ldo;
+    const void* resid;
+    const int32_t* idx;
+    int bf16;
+};
+
+constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
+
+__device__ __forceinline__ half8_t dequant8(uint32_t w, half2_t S, half2_t Zlo, half2_t Zhi) {
+    const uint32_t kMagic = 0x64006400u;
+    const half2_t sixteenth = {static_cast<half_t>(0.0625f), static_cast<half_t>(0.0625f)};
+    const uint32_t w8 = w >> 8;
+    const half2_t l0 = __builtin_bit_cast(half2_t, (w & 0x000f000fu) | kMagic);
+    const half2_t h0 = __builtin_bit_cast(half2_t, (w & 0x00f000f0u) | kMagic);
+    const half2_t l1 = __builtin_bit_cast(half2_t, (w8 & 0x000f000fu) | kMagic);
+    const half2_t h1 = __builtin_bit_cast(half2_t, (w8 & 0x00f000f0u) | kMagic);
+    const half2_t p0 = (l0 - Zlo) * S;
+    const half2_t p1 = __builtin_elementwise_fma(h0, sixteenth, -Zhi) * S;
+    const half2_t p2 = (l1 - Zlo) * S;
+    const half2_t p3 = __builtin_elementwise_fma(h1, sixteenth, -Zhi) * S;
+    half8_t r;
+    r[0] = p0[0]; r[1] = p0[1]; r[2] = p1[0]; r[3] = p1[1];
+    r[4] = p2[0]; r[5] = p2[1]; r[6] = p3[0]; r[7] = p3[1];
+    return r;
+}
+
+struct ScaleZero {
+    half2_t S, Zlo, Zhi;
+};
+__device__ __forceinline__ ScaleZero expand_sz(uint32_t raw) {
+    const half2_t sz = __builtin_bit_cast(half2_t, raw);       // [0] = scale, [1] = zero-point
+    ScaleZero r;
+    r.S = half2_t{sz[0], sz[0]};
+    const half_t zlo = sz[1] + static_cast<half_t>(1024.0f);
+    const half_t zhi = sz[1] + static_cast<half_t>(64.0f);
+    r.Zlo = half2_t{zlo, zlo};
+    r.Zhi = half2_t{zhi, zhi};
+    return r;
+}
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+template <int WM, int WN, int FM, int FN, int GPT, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64)
+gemm_w4a16_kernel(GemmDev p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * FM * 32;
+    constexpr int A_LOADS = (BM * 8) / NT;
+    static_assert((BM * 8) % NT == 0, "A tile must split evenly over the threads");
+    static_assert(EPI != EPI_SWIGLU_F16 || (FN % 2) == 0, "gate/up fragments come in pairs");
+
+    __shared__ __attribute__((aligned(16))) half_t As[2][BM * kLdsStride];
+
+    const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
+    const int tile_m = blockIdx.x % p.tiles_m;
+    const int tile_n = blockIdx.x / p.tiles_m;
+    const int m0 = tile_m * BM;
+    if (m0 >= M) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WM;
+    const int wn = wave / WM;
+    const int l32 = lane & 31;
+    const int lhi = lane >> 5;
+
+    // ---- which weight fragments this wave owns --------------------------------------------------
+    const U4* bp[FN];
+    const uint32_t* sp[FN];
+    int npad[FN], mat_of[FN], frag_of[FN];
+    bool valid[FN];
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        int vf = (tile_n * WN + wn) * FN + fn;
+        valid[fn] = vf < p.vf_total;
+        if (!valid[fn]) vf = p.vf_total - 1;
+        int mat, f;
+        if (EPI == EPI_SWIGLU_F16) {
+            mat = vf & 1;
+            f = vf >> 1;
+        } else {
+            mat = 0;
+            f = vf;
+            if (p.n_w > 1 && f >= p.NF[0]) { f -= p.NF[0]; mat = 1; }
+            if (p.n_w > 2 && mat == 1 && f >= p.NF[1]) { f -= p.NF[1]; mat = 2; }
+        }
+        mat_of[fn] = mat;
+        frag_of[fn] = f;
+        bp[fn] = p.codes[mat] + static_cast<size_t>(f) * p.KT * 64 + lane;
+        sp[fn] = p.sz[mat] + f * 32 + l32;
+        npad[fn] = p.npad[mat];
+    }
+
+    float16_t acc[FM][FN];
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.0f;
+
+    // ---- A tile: global -> registers -> LDS ------------------------------------------------------
+    U4 areg[A_LOADS];
+    const half_t* a_src[A_LOADS];
+    int a_dst[A_LOADS], a_col[A_LOADS];
+#pragma unroll
+    for (int it = 0; it < A_LOADS; ++it) {
+        const int c = it * NT + tid;
+        const int row = c >> 3, col8 = c & 7;
+        const int gr = min(m0 + row, M - 1);
+        a_src[it] = p.A + static_cast<size_t>(gr) * p.K + col8 * 8;
+        a_dst[it] = row * kLdsStride + col8 * 8;
+        a_col[it] = col8 * 8;
+    }
+    auto load_a = [&](int kt) {
+#pragma unroll
+        for (int it = 0; it < A_LOADS; ++it) {
+            if (kt * 64 + a_col[it] < p.K)
+                areg[it] = *reinterpret_cast<const U4*>(a_src[it] + kt * 64);
+            else
+                areg[it] = U4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < A_LOADS; ++it) *reinterpret_cast<U4*>(&As[buf][a_dst[it]]) = areg[it];
+    };
+
+    U4 bq[FN], bq_next[FN];
+    uint32_t szraw[FN][GPT], szraw_next[FN][GPT];
+    auto load_b = [&](int kt, U4* dst, uint32_t (*sz)[GPT]) {
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) {
+            dst[fn] = bp[fn][static_cast<size_t>(kt) * 64];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) {
+                const int gi = (kt * 64 + g * 32) >> p.gshift;
+                sz[fn][g] = sp[fn][static_cast<size_t>(gi) * npad[fn]];
+            }
+        }
+    };
+
+    load_a(0);
+    load_b(0, bq, szraw);
+    store_a(0);
+    __syncthreads();
+
+    const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
+    for (int kt = 0; kt < p.KT; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < p.KT;
+        if (more) {
+            load_a(kt + 1);
+            load_b(kt + 1, bq_next, szraw_next);
+        }
+        ScaleZero sz[FN][GPT];
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(szraw[fn][g]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            half8_t a[FM];
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm)
+                a[fm] = *reinterpret_cast<const half8_t*>(&As[cur][a_row0 + fm * 32 * kLdsStride + j * 16]);
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                const uint32_t wj = j == 0 ? bq[fn].x : j == 1 ? bq[fn].y : j == 2 ? bq[fn].z : bq[fn].w;
+                const ScaleZero& s = sz[fn][GPT == 2 ? (j >> 1) : 0];
+                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fm], b, acc[fm][fn], 0, 0, 0);
+            }
+        }
+        if (more) {
+            store_a(cur ^ 1);
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                bq[fn] = bq_next[fn];
+#pragma unroll
+                for (int g = 0; g < GPT; ++g) szraw[fn][g] = szraw_next[fn][g];
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue -------------------------------------------------------------------------------
+    // accumulator register r of a lane holds C[row][col] with col = lane%32 and
+    // row = 8*(r/4) + 4*(lane/32) + r%4 inside the 32x32 fragment.
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        const int rbase = m0 + (wm * FM + fm) * 32 + 4 * lhi;
+#pragma unroll
+        for (int fn = 0; fn < FN; fn += (EPI == EPI_SWIGLU_F16 ? 2 : 1)) {
+            if (!valid[fn]) continue;
+            const int mat = mat_of[fn];
+            const int ncol = frag_of[fn] * 32 + l32;
+            if (ncol >= p.N[mat]) continue;
+            const int col = (EPI == EPI_SWIGLU_F16 ? 0 : p.colbase[mat]) + ncol;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = rbase + 8 * (r >> 2) + (r & 3);
+                if (row >= M) continue;
+                if (EPI == EPI_STORE_F16) {
+                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(row) * p.ldo + col] =
+                        float_to_half_bits(acc[fm][fn][r]);
+                } else if (EPI == EPI_SWIGLU_F16) {
+                    const float v = silu_f(acc[fm][fn][r]) * acc[fm][fn + 1][r];
+                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(row) * p.ldo + col] = float_to_half_bits(v);
+                } else if (EPI == EPI_RESID_F32) {
+                    const int t = p.idx[row];
+                    const float xv = act_to_float(reinterpret_cast<const uint16_t*>(p.resid)[static_cast<size_t>(t) * p.ldo + col], p.bf16);
+                    reinterpret_cast<float*>(p.out)[static_cast<size_t>(row) * p.ldo + col] = xv + acc[fm][fn][r];
+                } else {
+                    const int t = p.idx[row];
+                    const float hv = reinterpret_cast<const float*>(p.resid)[static_cast<size_t>(row) * p.ldo + col];
+                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(t) * p.ldo + col] =
+                        float_to_act(hv + acc[fm][fn][r], p.bf16);
+                }
+            }
+        }
+    }
+}
+
+template <int WM, int WN, int FM, int FN, int GPT, int EPI>
+static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
+    constexpr int BM = WM * FM * 32;
+    constexpr int BNF = WN * FN;
+    d.tiles_m = (d.M_max + BM - 1) / BM;
+    d.tiles_n = (d.vf_total + BNF - 1) / BNF;
+    const int blocks = d.tiles_m * d.tiles_n;
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+    return hipGetLastError();
+}
+
+template <int GPT, int EPI>
+static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
+    if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI>(d, stream);
+    return launch_cfg<2, 2, 4, 4, GPT, EPI>(d, stream);
+}
+
+template <int GPT>
+static hipError_t launch_gpt(GemmDev& d, int epi, hipStream_t stream) {
+    switch (epi) {
+        case EPI_STORE_F16: return launch_epi<GPT, EPI_STORE_F16>(d, stream);
+        case EPI_RESID_F32: return launch_epi<GPT, EPI_RESID_F32>(d, stream);
+        case EPI_SWIGLU_F16: return launch_epi<GPT, EPI_SWIGLU_F16>(d, stream);
+        default: return launch_epi<GPT, EPI_RESID_SCATTER>(d, stream);
+    }
+}
+
+hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
+    if (a.M_max <= 0) return hipSuccess;
+    GemmDev d{};
+    d.A = reinterpret_cast<const half_t*>(a.A);
+    d.count = a.count;
+    d.M_max = a.M_max;
+    d.K = a.K;
+    d.KT = (a.K + 63) / 64;
+    d.gshift = a.group == 32 ? 5 : a.group == 64 ? 6 : 7;
+    d.n_w = a.n_w;
+    int col = 0, vf = 0;
+    for (int i = 0; i < 3; ++i) {
+        const int j = i < a.n_w ? i : 0;
+        const PrepackDims pd = prepack_dims(a.w[j].N, a.w[j].K, a.group);
+        d.codes[i] = reinterpret_cast<const U4*>(a.w[j].prepacked);
+        d.sz[i] = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(a.w[j].prepacked) + pd.code_bytes);
+        d.N[i] = a.w[j].N;
+        d.NF[i] = pd.NF;
+        d.npad[i] = pd.NF * 32;
+        d.colbase[i] = col;
+        if (i < a.n_w) { col += a.w[j].N; vf += pd.NF; }
+    }
+    d.vf_total = vf;
+    d.out = a.out;
+    d.ldo = a.ldo;
+    d.resid = a.resid;
+    d.idx = a.idx;
+    d.bf16 = a.bf16;
+    if (a.group == 32) return launch_gpt<2>(d, a.epilogue, stream);
+    return launch_gpt<1>(d, a.epilogue, stream);
+}
+
+}  // namespace qtale

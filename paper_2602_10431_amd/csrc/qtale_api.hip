@@ -1,0 +1,494 @@
+// Host side of the C ABI declared in include/qtale.h: argument validation (before any HIP call),
+// workspace carving, and the launch sequence of one token-adaptive layer:
+//   router score -> select/compact -> gather+RMSNorm -> q|k|v GEMM -> rotary (+cache append) ->
+//   attention over executed tokens -> o GEMM (+residual) -> RMSNorm -> gate/up GEMM (SiLU*up) ->
+//   down GEMM (+residual, scatter back).
+// In ratio mode the executed count k is known on the host, so every launch shape is static and the
+// stack runs without any device->host synchronisation; in threshold mode grids are sized for all T
+// tokens and the kernels read the device-side count.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/qtale.h"
+#include "qtale_kernels.h"
+
+using namespace qtale;
+
+struct qtale_ctx {
+    int mode = QTALE_MODE_RATIO;
+    float value = 1.0f;
+    bool profiling = false;
+    struct Span { int cls; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> free_events;
+    double ms[QTALE_PROF_CLASSES] = {0};
+    int64_t launches[QTALE_PROF_CLASSES] = {0};
+};
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Workspace {
+    float* z;
+    int32_t* idx;
+    int32_t* scalars;      // [0] count, [1] n_items
+    int32_t* cu_exec;
+    int32_t* row_seq;
+    int32_t* kv_old;
+    void* items;
+    void* nbuf;            // [T][H] fp16
+    void* qkv;             // [T][(nh+2nkv)d] fp16
+    void* attn;            // [T][nh d] fp16
+    float* h;              // [T][H] fp32
+    void* act;             // [T][I] fp16
+    size_t total;
+};
+
+Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
+    Workspace w{};
+    size_t off = 0;
+    char* p = reinterpret_cast<char*>(base);
+    auto take = [&](size_t bytes) {
+        void* r = p ? p + off : nullptr;
+        off += align_up(bytes, 256);
+        return r;
+    };
+    const size_t Tz = static_cast<size_t>(T);
+    w.z = reinterpret_cast<float*>(take(Tz * 4));
+    w.idx = reinterpret_cast<int32_t*>(take(Tz * 4));
+    w.scalars = reinterpret_cast<int32_t*>(take(256));
+    w.cu_exec = reinterpret_cast<int32_t*>(take((static_cast<size_t>(B) + 1) * 4));
+    w.row_seq = reinterpret_cast<int32_t*>(take(Tz * 4));
+    w.kv_old = reinterpret_cast<int32_t*>(take(static_cast<size_t>(B) * 4 + 4));
+    w.items = take((Tz / kAttnBQ + B + 2) * 8);
+    w.nbuf = take(Tz * c->hidden * 2);
+    w.qkv = take(Tz * (static_cast<size_t>(c->n_heads) + 2 * c->n_kv_heads) * c->head_dim * 2);
+    w.attn = take(Tz * c->n_heads * c->head_dim * 2);
+    w.h = reinterpret_cast<float*>(take(Tz * c->hidden * 4));
+    w.act = take(Tz * c->inter * 2);
+    w.total = off;
+    return w;
+}
+
+int check_quant_params(int N, int K, int bits, int group) {
+    if (N <= 0 || K <= 0) return QTALE_ERR_INVALID_ARG;
+    if (bits != 4) return QTALE_ERR_UNSUPPORTED;
+    if (group != 32 && group != 64 && group != 128) return QTALE_ERR_UNSUPPORTED;
+    if (K % 8 != 0) return QTALE_ERR_SHAPE;
+    return QTALE_OK;
+}
+
+int check_cfg(const qtale_layer_cfg* c) {
+    if (!c) return QTALE_ERR_INVALID_ARG;
+    if (c->hidden <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->inter <= 0)
+        return QTALE_ERR_INVALID_ARG;
+    if (c->bits != 4) return QTALE_ERR_UNSUPPORTED;
+    if (c->group != 32 && c->group != 64 && c->group != 128) return QTALE_ERR_UNSUPPORTED;
+    if (c->head_dim != 64 && c->head_dim != 128) return QTALE_ERR_UNSUPPORTED;
+    if (c->act_dtype != QTALE_ACT_FP16 && c->act_dtype != QTALE_ACT_BF16) return QTALE_ERR_UNSUPPORTED;
+    if (c->n_heads % c->n_kv_heads != 0) return QTALE_ERR_SHAPE;
+    if (c->hidden % 8 != 0 || c->inter % 8 != 0) return QTALE_ERR_SHAPE;
+    if (!(c->rms_eps >= 0.0f) || !(c->rope_base > 0.0f)) return QTALE_ERR_INVALID_ARG;
+    return QTALE_OK;
+}
+
+int check_linear(const qtale_qlinear& l, int N, int K) {
+    if (!l.prepacked) return QTALE_ERR_INVALID_ARG;
+    if (l.N != N || l.K != K) return QTALE_ERR_SHAPE;
+    return QTALE_OK;
+}
+
+int check_weights(const qtale_layer_cfg* c, const qtale_layer_weights* w) {
+    if (!w) return QTALE_ERR_INVALID_ARG;
+    const int H = c->hidden, qd = c->n_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim;
+    int e;
+    if ((e = check_linear(w->q, qd, H))) return e;
+    if ((e = check_linear(w->k, kd, H))) return e;
+    if ((e = check_linear(w->v, kd, H))) return e;
+    if ((e = check_linear(w->o, H, qd))) return e;
+    if ((e = check_linear(w->gate, c->inter, H))) return e;
+    if ((e = check_linear(w->up, c->inter, H))) return e;
+    if ((e = check_linear(w->down, H, c->inter))) return e;
+    if (!w->norm1 || !w->norm2 || !w->router_w) return QTALE_ERR_INVALID_ARG;
+    if (std::isnan(w->router_b)) return QTALE_ERR_INVALID_ARG;
+    return QTALE_OK;
+}
+
+// k = floor(r*T + 1/2) in double, clamped.
+int executed_count(float r, int T) {
+    const double v = std::floor(static_cast<double>(r) * static_cast<double>(T) + 0.5);
+    if (v <= 0.0) return 0;
+    if (v >= static_cast<double>(T)) return T;
+    return static_cast<int>(v);
+}
+
+float theta_to_logit(float theta) {
+    const double t = static_cast<double>(theta);
+    if (t <= 0.0) return -INFINITY;
+    if (t >= 1.0) return INFINITY;
+    return static_cast<float>(std::log(t / (1.0 - t)));
+}
+
+struct Prof {
+    qtale_ctx* ctx;
+    hipStream_t stream;
+    int cls;
+    hipEvent_t a = nullptr, b = nullptr;
+    bool on;
+    static hipEvent_t get(qtale_ctx* c) {
+        if (!c->free_events.empty()) {
+            hipEvent_t e = c->free_events.back();
+            c->free_events.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+    Prof(qtale_ctx* c, hipStream_t s, int k) : ctx(c), stream(s), cls(k), on(c->profiling) {
+        if (!on) return;
+        a = get(c);
+        b = get(c);
+        if (!a || !b) { on = false; return; }
+        (void)hipEventRecord(a, stream);
+    }
+    ~Prof() {
+        if (!on) return;
+        (void)hipEventRecord(b, stream);
+        ctx->spans.push_back({cls, a, b});
+    }
+};
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return QTALE_ERR_HIP;    \
+    } while (0)
+
+int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_layer_weights* w, void* x, int T,
+                       const int32_t* seq_offsets, int B, const int32_t* positions, const qtale_kv* kv,
+                       int32_t* sel_idx, int32_t* sel_count, float* scores, const Workspace& ws,
+                       hipStream_t stream) {
+    const int bf16 = c->act_dtype == QTALE_ACT_BF16;
+    const int H = c->hidden, nh = c->n_heads, nkv = c->n_kv_heads, d = c->head_dim, I = c->inter;
+    const int ratio_mode = ctx->mode == QTALE_MODE_RATIO;
+    const int k = ratio_mode ? executed_count(ctx->value, T) : 0;
+    const int M_max = ratio_mode ? k : T;
+    float* z = scores ? scores : ws.z;
+    int32_t* count = ws.scalars;
+
+    {
+        Prof pr(ctx, stream, 0);
+        HIP_TRY(launch_router_score(x, bf16, T, H, w->router_w, w->router_b, z, stream));
+    }
+    {
+        Prof pr(ctx, stream, 1);
+        SelectArgs s{};
+        s.z = z; s.T = T; s.mode = ratio_mode ? 0 : 1; s.k = k;
+        s.z_thr = ratio_mode ? 0.0f : theta_to_logit(ctx->value);
+        s.seq_offsets = seq_offsets; s.B = B;
+        s.idx = ws.idx; s.count = count; s.cu_exec = ws.cu_exec; s.row_seq = ws.row_seq;
+        s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old;
+        s.idx_copy = sel_idx; s.count_copy = sel_count;
+        HIP_TRY(launch_select(s, stream));
+    }
+    if (M_max == 0) return QTALE_OK;
+    {
+        Prof pr(ctx, stream, 2);
+        HIP_TRY(launch_gather_rmsnorm(x, bf16, H, ws.idx, count, M_max, w->norm1, c->rms_eps, ws.nbuf, stream));
+    }
+    const int qkv_w = (nh + 2 * nkv) * d;
+    {
+        Prof pr(ctx, stream, 3);
+        GemmArgs g{};
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.n_w = 3;
+        g.w[0] = {w->q.prepacked, w->q.N, w->q.K};
+        g.w[1] = {w->k.prepacked, w->k.N, w->k.K};
+        g.w[2] = {w->v.prepacked, w->v.N, w->v.K};
+        g.epilogue = EPI_STORE_F16; g.out = ws.qkv; g.ldo = qkv_w;
+        HIP_TRY(launch_gemm_w4a16(g, stream));
+    }
+    {
+        Prof pr(ctx, stream, 4);
+        RopeArgs r{};
+        r.qkv = ws.qkv; r.nh = nh; r.nkv = nkv; r.d = d; r.base = c->rope_base;
+        r.idx = ws.idx; r.positions = positions; r.count = count; r.max_rows = M_max;
+        if (kv) { r.k_cache = kv->k_cache; r.v_cache = kv->v_cache; r.cap = kv->cap; }
+        r.row_seq = ws.row_seq; r.cu_exec = ws.cu_exec; r.kv_old = ws.kv_old;
+        HIP_TRY(launch_rope_append(r, stream));
+    }
+    {
+        Prof pr(ctx, stream, 5);
+        AttnArgs a{};
+        a.qkv = ws.qkv; a.out = ws.attn; a.nh = nh; a.nkv = nkv; a.d = d; a.count = count; a.max_rows = M_max;
+        a.B = B; a.cu_exec = ws.cu_exec; a.row_seq = ws.row_seq;
+        if (kv) { a.k_cache = kv->k_cache; a.v_cache = kv->v_cache; a.cap = kv->cap; }
+        a.kv_old = ws.kv_old; a.T = T; a.items = ws.items; a.n_items = ws.scalars + 1;
+        HIP_TRY(launch_attention(a, stream));
+    }
+    {
+        Prof pr(ctx, stream, 6);
+        GemmArgs g{};
+        g.A = ws.attn; g.count = count; g.M_max = M_max; g.K = nh * d; g.group = c->group; g.n_w = 1;
+        g.w[0] = {w->o.prepacked, w->o.N, w->o.K};
+        g.epilogue = EPI_RESID_F32; g.out = ws.h; g.ldo = H; g.resid = x; g.idx = ws.idx; g.bf16 = bf16;
+        HIP_TRY(launch_gemm_w4a16(g, stream));
+    }
+    {
+        Prof pr(ctx, stream, 7);
+        HIP_TRY(launch_rmsnorm_f32(ws.h, H, count, M_max, w->norm2, bf16, c->rms_eps, ws.nbuf, stream));
+    }
+    {
+        Prof pr(ctx, stream, 8);
+        GemmArgs g{};
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.n_w = 2;
+        g.w[0] = {w->gate.prepacked, w->gate.N, w->gate.K};
+        g.w[1] = {w->up.prepacked, w->up.N, w->up.K};
+        g.epilogue = EPI_SWIGLU_F16; g.out = ws.act; g.ldo = I;
+        HIP_TRY(launch_gemm_w4a16(g, stream));
+    }
+    {
+        Prof pr(ctx, stream, 9);
+        GemmArgs g{};
+        g.A = ws.act; g.count = count; g.M_max = M_max; g.K = I; g.group = c->group; g.n_w = 1;
+        g.w[0] = {w->down.prepacked, w->down.N, w->down.K};
+        g.epilogue = EPI_RESID_SCATTER; g.out = x; g.ldo = H; g.resid = ws.h; g.idx = ws.idx; g.bf16 = bf16;
+        HIP_TRY(launch_gemm_w4a16(g, stream));
+    }
+    return QTALE_OK;
+}
+
+int check_forward_args(qtale_ctx* ctx, const qtale_layer_cfg* cfg, void* x, int T, const int32_t* seq_offsets,
+                       int B, const int32_t* positions, void* workspace, size_t workspace_bytes) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    int e = check_cfg(cfg);
+    if (e) return e;
+    if (T < 0 || B < 0) return QTALE_ERR_INVALID_ARG;
+    if (T == 0) return QTALE_OK;
+    if (!x || !seq_offsets || !positions || B == 0) return QTALE_ERR_INVALID_ARG;
+    if (!workspace) return QTALE_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return QTALE_ERR_INVALID_ARG;
+    if (workspace_bytes < carve(cfg, T, B, nullptr).total) return QTALE_ERR_WORKSPACE_TOO_SMALL;
+    return QTALE_OK;
+}
+
+int check_kv(const qtale_kv* kv) {
+    if (!kv) return QTALE_OK;
+    if (!kv->k_cache || !kv->v_cache || !kv->kv_len || kv->cap <= 0) return QTALE_ERR_INVALID_ARG;
+    return QTALE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* qtale_strerror(int code) {
+    switch (code) {
+        case QTALE_OK: return "ok";
+        case QTALE_ERR_INVALID_ARG: return "invalid argument";
+        case QTALE_ERR_SHAPE: return "inconsistent or unsupported shape";
+        case QTALE_ERR_UNSUPPORTED: return "unsupported bits / group / head_dim / dtype";
+        case QTALE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case QTALE_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int qtale_create(qtale_ctx** out) {
+    if (!out) return QTALE_ERR_INVALID_ARG;
+    *out = new (std::nothrow) qtale_ctx();
+    return *out ? QTALE_OK : QTALE_ERR_INVALID_ARG;
+}
+
+int qtale_destroy(qtale_ctx* ctx) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    for (auto& s : ctx->spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+    for (auto e : ctx->free_events) (void)hipEventDestroy(e);
+    delete ctx;
+    return QTALE_OK;
+}
+
+int qtale_set_exec_ratio(qtale_ctx* ctx, float r) {
+    if (!ctx || std::isnan(r) || r < 0.0f || r > 1.0f) return QTALE_ERR_INVALID_ARG;
+    ctx->mode = QTALE_MODE_RATIO;
+    ctx->value = r;
+    return QTALE_OK;
+}
+
+int qtale_set_threshold(qtale_ctx* ctx, float theta) {
+    if (!ctx || std::isnan(theta)) return QTALE_ERR_INVALID_ARG;
+    ctx->mode = QTALE_MODE_THRESHOLD;
+    ctx->value = theta;
+    return QTALE_OK;
+}
+
+int qtale_get_control(const qtale_ctx* ctx, int* mode, float* value) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    if (mode) *mode = ctx->mode;
+    if (value) *value = ctx->value;
+    return QTALE_OK;
+}
+
+size_t qtale_prepacked_bytes(int N, int K, int bits, int group) {
+    if (check_quant_params(N, K, bits, group) != QTALE_OK) return 0;
+    const PrepackDims d = prepack_dims(N, K, group);
+    return d.code_bytes + d.sz_bytes;
+}
+
+int qtale_quantize(const float* W, int N, int K, int bits, int group, uint32_t* codes, uint16_t* scales,
+                   uint16_t* zeros, void* prepacked, void* stream) {
+    const int e = check_quant_params(N, K, bits, group);
+    if (e) return e;
+    if (!W || !codes || !scales || !zeros) return QTALE_ERR_INVALID_ARG;
+    if (prepacked && reinterpret_cast<uintptr_t>(prepacked) % 16 != 0) return QTALE_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    HIP_TRY(launch_quantize(W, N, K, bits, group, codes, scales, zeros, s));
+    if (prepacked) HIP_TRY(launch_prepack(codes, scales, zeros, N, K, group, prepacked, s));
+    return QTALE_OK;
+}
+
+int qtale_prepack(const uint32_t* codes, const uint16_t* scales, const uint16_t* zeros, int N, int K, int bits,
+                  int group, void* prepacked, void* stream) {
+    const int e = check_quant_params(N, K, bits, group);
+    if (e) return e;
+    if (!codes || !scales || !zeros || !prepacked) return QTALE_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(prepacked) % 16 != 0) return QTALE_ERR_INVALID_ARG;
+    HIP_TRY(launch_prepack(codes, scales, zeros, N, K, group, prepacked, reinterpret_cast<hipStream_t>(stream)));
+    return QTALE_OK;
+}
+
+size_t qtale_workspace_bytes(const qtale_layer_cfg* cfg, int max_tokens, int max_seqs) {
+    if (check_cfg(cfg) != QTALE_OK || max_tokens < 0 || max_seqs < 0) return 0;
+    return carve(cfg, max_tokens, max_seqs, nullptr).total;
+}
+
+int qtale_layer_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* w, void* x, int T,
+                        const int32_t* seq_offsets, int B, const int32_t* positions, const qtale_kv* kv,
+                        int32_t* sel_idx, int32_t* sel_count, float* scores, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    int e = check_forward_args(ctx, cfg, x, T, seq_offsets, B, positions, workspace, workspace_bytes);
+    if (e) return e;
+    if (T == 0) return QTALE_OK;
+    if ((e = check_weights(cfg, w))) return e;
+    if ((e = check_kv(kv))) return e;
+    const Workspace ws = carve(cfg, T, B, workspace);
+    return layer_forward_impl(ctx, cfg, w, x, T, seq_offsets, B, positions, kv, sel_idx, sel_count, scores, ws,
+                              reinterpret_cast<hipStream_t>(stream));
+}
+
+int qtale_stack_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* layers,
+                        int n_layers, void* x, int T, const int32_t* seq_offsets, int B, const int32_t* positions,
+                        const qtale_kv* kv_per_layer, int32_t* sel_idx, int32_t* sel_count, float* scores,
+                        void* dbg_hidden, void* workspace, size_t workspace_bytes, void* stream) {
+    int e = check_forward_args(ctx, cfg, x, T, seq_offsets, B, positions, workspace, workspace_bytes);
+    if (e) return e;
+    if (n_layers < 0 || (n_layers > 0 && !layers)) return QTALE_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+        if ((e = check_weights(cfg, &layers[l]))) return e;
+        if (kv_per_layer && (e = check_kv(&kv_per_layer[l]))) return e;
+    }
+    if (T == 0) return QTALE_OK;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const Workspace ws = carve(cfg, T, B, workspace);
+    const size_t row_bytes = static_cast<size_t>(cfg->hidden) * 2;
+    for (int l = 0; l < n_layers; ++l) {
+        if (dbg_hidden) {
+            HIP_TRY(hipMemcpyAsync(reinterpret_cast<char*>(dbg_hidden) + static_cast<size_t>(l) * T * row_bytes, x,
+                                   static_cast<size_t>(T) * row_bytes, hipMemcpyDeviceToDevice, s));
+        }
+        e = layer_forward_impl(ctx, cfg, &layers[l], x, T, seq_offsets, B, positions,
+                               kv_per_layer ? &kv_per_layer[l] : nullptr,
+                               sel_idx ? sel_idx + static_cast<size_t>(l) * T : nullptr,
+                               sel_count ? sel_count + l : nullptr,
+                               scores ? scores + static_cast<size_t>(l) * T : nullptr, ws, s);
+        if (e) return e;
+    }
+    return QTALE_OK;
+}
+
+int qtale_router_select(qtale_ctx* ctx, int act_dtype, const void* x, int T, int hidden, const float* router_w,
+                        float router_b, const int32_t* seq_offsets, int B, float* scores, int32_t* sel_idx,
+                        int32_t* sel_count, int32_t* cu_exec, void* stream) {
+    if (!ctx || T < 0 || B < 0 || hidden <= 0) return QTALE_ERR_INVALID_ARG;
+    if (act_dtype != QTALE_ACT_FP16 && act_dtype != QTALE_ACT_BF16) return QTALE_ERR_UNSUPPORTED;
+    if (hidden % 8 != 0) return QTALE_ERR_SHAPE;
+    if (std::isnan(router_b)) return QTALE_ERR_INVALID_ARG;
+    if (T == 0) return QTALE_OK;
+    if (!x || !router_w || !scores || !sel_idx || !sel_count) return QTALE_ERR_INVALID_ARG;
+    if (cu_exec && (!seq_offsets || B == 0)) return QTALE_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    HIP_TRY(launch_router_score(x, act_dtype == QTALE_ACT_BF16, T, hidden, router_w, router_b, scores, s));
+    SelectArgs a{};
+    a.z = scores; a.T = T;
+    a.mode = ctx->mode == QTALE_MODE_RATIO ? 0 : 1;
+    a.k = ctx->mode == QTALE_MODE_RATIO ? executed_count(ctx->value, T) : 0;
+    a.z_thr = ctx->mode == QTALE_MODE_RATIO ? 0.0f : theta_to_logit(ctx->value);
+    a.seq_offsets = seq_offsets; a.B = cu_exec ? B : 0;
+    a.idx = sel_idx; a.count = sel_count; a.cu_exec = cu_exec;
+    if (!cu_exec) a.B = -1;            // skip the per-sequence tail entirely
+    HIP_TRY(launch_select(a, s));
+    return QTALE_OK;
+}
+
+int qtale_linear_w4a16(const qtale_qlinear* w, int group, const void* A, int M, void* out, void* stream) {
+    if (!w || M < 0) return QTALE_ERR_INVALID_ARG;
+    int e = check_quant_params(w->N, w->K, 4, group);
+    if (e) return e;
+    if (M == 0) return QTALE_OK;
+    if (!w->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
+    GemmArgs g{};
+    g.A = A; g.M_max = M; g.K = w->K; g.group = group; g.n_w = 1;
+    g.w[0] = {w->prepacked, w->N, w->K};
+    g.epilogue = EPI_STORE_F16; g.out = out; g.ldo = w->N;
+    HIP_TRY(launch_gemm_w4a16(g, reinterpret_cast<hipStream_t>(stream)));
+    return QTALE_OK;
+}
+
+int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int group, const void* A, int M,
+                       void* out, void* stream) {
+    if (!gate || !up || M < 0) return QTALE_ERR_INVALID_ARG;
+    int e = check_quant_params(gate->N, gate->K, 4, group);
+    if (e) return e;
+    if (gate->N != up->N || gate->K != up->K) return QTALE_ERR_SHAPE;
+    if (M == 0) return QTALE_OK;
+    if (!gate->prepacked || !up->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
+    GemmArgs g{};
+    g.A = A; g.M_max = M; g.K = gate->K; g.group = group; g.n_w = 2;
+    g.w[0] = {gate->prepacked, gate->N, gate->K};
+    g.w[1] = {up->prepacked, up->N, up->K};
+    g.epilogue = EPI_SWIGLU_F16; g.out = out; g.ldo = gate->N;
+    HIP_TRY(launch_gemm_w4a16(g, reinterpret_cast<hipStream_t>(stream)));
+    return QTALE_OK;
+}
+
+int qtale_profile_enable(qtale_ctx* ctx, int on) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    ctx->profiling = on != 0;
+    return QTALE_OK;
+}
+
+int qtale_profile_read(qtale_ctx* ctx, double* ms, int64_t* launches) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    for (auto& s : ctx->spans) {
+        float t = 0.0f;
+        if (hipEventSynchronize(s.b) != hipSuccess) return QTALE_ERR_HIP;
+        if (hipEventElapsedTime(&t, s.a, s.b) != hipSuccess) return QTALE_ERR_HIP;
+        ctx->ms[s.cls] += t;
+        ctx->launches[s.cls] += 1;
+        ctx->free_events.push_back(s.a);
+        ctx->free_events.push_back(s.b);
+    }
+    ctx->spans.clear();
+    for (int i = 0; i < QTALE_PROF_CLASSES; ++i) {
+        if (ms) ms[i] = ctx->ms[i];
+        if (launches) launches[i] = ctx->launches[i];
+        ctx->ms[i] = 0.0;
+        ctx->launches[i] = 0;
+    }
+    return QTALE_OK;
+}
+
+}  // extern "C"

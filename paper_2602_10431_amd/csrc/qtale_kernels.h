@@ -1,0 +1,110 @@
+// Host-side launchers of the gfx950 kernels (internal; the public boundary is include/qtale.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace qtale {
+
+struct PrepackDims {
+    int NF, KT, NGP;
+    size_t code_bytes, sz_bytes;
+};
+PrepackDims prepack_dims(int N, int K, int group);
+
+hipError_t launch_quantize(const float* W, int N, int K, int bits, int group, uint32_t* codes,
+                           uint16_t* scales, uint16_t* zeros, hipStream_t stream);
+hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const uint16_t* zeros, int N,
+                          int K, int group, void* prepacked, hipStream_t stream);
+
+// ---- router + selection --------------------------------------------------------------------
+hipError_t launch_router_score(const void* x, int bf16, int T, int H, const float* w, float b,
+                               float* z, hipStream_t stream);
+
+struct SelectArgs {
+    const float* z;            // [T]
+    int T;
+    int mode;                  // 0 ratio, 1 threshold
+    int k;                     // ratio mode: number of tokens to execute
+    float z_thr;               // threshold mode
+    const int32_t* seq_offsets;  // [B+1]
+    int B;
+    int32_t* idx;              // [T] out
+    int32_t* count;            // [1] out
+    int32_t* cu_exec;          // [B+1] out (nullable)
+    int32_t* row_seq;          // [T] out: sequence of each executed row (nullable)
+    int32_t* kv_len;           // [B] in/out (nullable): advanced by the executed count of each sequence
+    int32_t* kv_old;           // [B] out (nullable unless kv_len given): kv_len before the call
+    int32_t* idx_copy;         // nullable: second destination for idx (caller-visible output)
+    int32_t* count_copy;       // nullable
+};
+hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
+
+// ---- row operations ---------------------------------------------------------------------------
+// n1[i] = fp16(rmsnorm(x[idx[i]]) * gain) for i < *count
+hipError_t launch_gather_rmsnorm(const void* x, int bf16, int H, const int32_t* idx, const int32_t* count,
+                                 int max_rows, const void* gain, float eps, void* out_f16, hipStream_t stream);
+// n2[i] = fp16(rmsnorm(h[i]) * gain), h fp32
+hipError_t launch_rmsnorm_f32(const float* h, int H, const int32_t* count, int max_rows, const void* gain,
+                              int gain_bf16, float eps, void* out_f16, hipStream_t stream);
+
+struct RopeArgs {
+    void* qkv;                 // [rows][(nh+2nkv)*d] fp16, q and k rotated in place
+    int nh, nkv, d;
+    float base;
+    const int32_t* idx;        // compact row -> token
+    const int32_t* positions;  // [T]
+    const int32_t* count;
+    int max_rows;
+    // optional cache append
+    void* k_cache; void* v_cache; int cap;
+    const int32_t* row_seq; const int32_t* cu_exec; const int32_t* kv_old;
+};
+hipError_t launch_rope_append(const RopeArgs& a, hipStream_t stream);
+
+// ---- W4A16 GEMM ---------------------------------------------------------------------------------
+enum GemmEpilogue { EPI_STORE_F16 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU_F16 = 2, EPI_RESID_SCATTER = 3 };
+
+struct GemmWeights {
+    const void* prepacked;
+    int N, K;
+};
+
+struct GemmArgs {
+    const void* A;             // [M][K] fp16
+    const int32_t* count;      // device row count (nullable: use M_max)
+    int M_max;                 // host upper bound of rows (grid size)
+    int K;
+    int group;
+    int n_w;                   // number of weight matrices: 1, 2 (gate/up interleaved), 3 (q|k|v concatenated)
+    GemmWeights w[3];
+    int epilogue;
+    void* out;                 // STORE/SWIGLU: fp16 [M][ldo]; RESID_F32: fp32 [M][ldo]; RESID_SCATTER: act dtype x [T][ldo]
+    int ldo;
+    const void* resid;         // RESID_F32: x (act dtype, rows via idx); RESID_SCATTER: h fp32 [M][ldo]
+    const int32_t* idx;        // compact row -> token row (RESID_F32 reads, RESID_SCATTER writes)
+    int bf16;                  // act dtype of x
+};
+hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream);
+
+// ---- attention over executed tokens ---------------------------------------------------------------
+struct AttnArgs {
+    const void* qkv;           // [rows][(nh+2nkv)*d] fp16 (q rotated, k rotated, v)
+    void* out;                 // [rows][nh*d] fp16
+    int nh, nkv, d;
+    const int32_t* count;
+    int max_rows;              // host bound on executed rows
+    int B;
+    const int32_t* cu_exec;    // [B+1]
+    const int32_t* row_seq;    // [rows]
+    // cache (nullable): when given, keys/values are read from the cache only (new rows were appended)
+    const void* k_cache; const void* v_cache; int cap;
+    const int32_t* kv_old;     // [B]
+    int T;                     // tokens in the call
+    void* items;               // scratch: (max_rows / kAttnBQ + B) x int2 work list of the prefill kernel
+    int32_t* n_items;          // scratch [1]
+};
+constexpr int kAttnBQ = 128;   // executed rows per prefill-attention workgroup
+hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace qtale

@@ -1,0 +1,216 @@
+// Router score, threshold / top-k selection and order-preserving compaction (Eq. 2, Eq. 9, App. B.2).
+//
+// Score: z_t = fp32( sum_h fp64(x[t,h]) * fp64(w[h]) + fp64(b) ).  Products of a 16-bit activation and an
+// fp32 weight are exact in fp64, so the only order-dependent error is the fp64 summation, far below
+// the final fp32 rounding; the decision is then taken on the fp32 bit patterns, which makes the
+// executed set reproducible.
+// Decision (logit domain; sigmoid is strictly increasing so p_0 >= theta <=> z >= logit(theta)):
+//   threshold mode: execute iff z >= z_thr;
+//   ratio mode:     execute the k largest z, equal scores to the lower token index.
+#include "qtale_dev.h"
+#include "qtale_kernels.h"
+
+namespace qtale {
+
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+router_score_kernel(const uint16_t* __restrict__ x, int T, int H, const float* __restrict__ w, float b,
+                    float* __restrict__ z) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const U4* xr = reinterpret_cast<const U4*>(x + static_cast<size_t>(t) * H);
+    const float4* wr = reinterpret_cast<const float4*>(w);
+    double acc0 = 0.0, acc1 = 0.0;
+    const int chunks = H >> 3;
+    for (int c = lane; c < chunks; c += 64) {
+        const U4 xv = xr[c];
+        const float4 w0 = wr[2 * c], w1 = wr[2 * c + 1];
+        const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w};
+        const float ws[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const double a0 = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xs[i] & 0xffffu)));
+            const double a1 = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xs[i] >> 16)));
+            acc0 = fma(a0, static_cast<double>(ws[2 * i]), acc0);
+            acc1 = fma(a1, static_cast<double>(ws[2 * i + 1]), acc1);
+        }
+    }
+    double acc = wave_sum(acc0 + acc1);
+    if (lane == 0) z[t] = static_cast<float>(acc + static_cast<double>(b));
+}
+
+hipError_t launch_router_score(const void* x, int bf16, int T, int H, const float* w, float b, float* z,
+                               hipStream_t stream) {
+    if (T == 0) return hipSuccess;
+    const dim3 grid((T + 3) / 4), block(256);
+    if (bf16)
+        hipLaunchKernelGGL(router_score_kernel<true>, grid, block, 0, stream,
+                           reinterpret_cast<const uint16_t*>(x), T, H, w, b, z);
+    else
+        hipLaunchKernelGGL(router_score_kernel<false>, grid, block, 0, stream,
+                           reinterpret_cast<const uint16_t*>(x), T, H, w, b, z);
+    return hipGetLastError();
+}
+
+// fp32 -> uint32 key whose unsigned order is the float order (-0 is first folded onto +0).
+__device__ __forceinline__ uint32_t order_key(float f) {
+    f += 0.0f;
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kSelThreads = 1024;
+
+__device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t v, uint32_t* wsum, uint32_t& total) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    if (lane == 63) wsum[wid] = v;
+    __syncthreads();
+    if (wid == 0) {
+        uint32_t w = lane < (kSelThreads / 64) ? wsum[lane] : 0u;
+#pragma unroll
+        for (int o = 1; o < kSelThreads / 64; o <<= 1) {
+            const uint32_t t = __shfl_up(w, o, 64);
+            if (lane >= o) w += t;
+        }
+        if (lane < kSelThreads / 64) wsum[lane] = w;
+    }
+    __syncthreads();
+    if (wid > 0) v += wsum[wid - 1];
+    total = wsum[kSelThreads / 64 - 1];
+    __syncthreads();
+    return v;
+}
+
+// One workgroup selects and compacts: four 8-bit radix passes find the k-th largest key, one ordered
+// pass writes ascending indices, the tail derives per-sequence counts and advances the cache lengths.
+__global__ void __launch_bounds__(kSelThreads)
+select_compact_kernel(SelectArgs a) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wsum[kSelThreads / 64];
+    __shared__ uint32_t s_prefix, s_krem;
+    const int tid = threadIdx.x;
+    const int T = a.T;
+    uint32_t kth, need_eq;
+    if (a.mode == 0) {
+        if (a.k <= 0) {
+            kth = 0xffffffffu;
+            need_eq = 0u;
+        } else {
+            uint32_t prefix = 0u, krem = static_cast<uint32_t>(a.k);
+            for (int pass = 0; pass < 4; ++pass) {
+                const int shift = 24 - 8 * pass;
+                if (tid < 256) hist[tid] = 0u;
+                __syncthreads();
+                for (int t = tid; t < T; t += kSelThreads) {
+                    const uint32_t key = order_key(a.z[t]);
+                    if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
+                __syncthreads();
+                if (tid < 64) {
+                    const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+                    const uint32_t s = h0 + h1 + h2 + h3;
+                    uint32_t suf = s;                        // inclusive sum over lanes >= tid
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const uint32_t t = __shfl_down(suf, o, 64);
+                        if (tid + o < 64) suf += t;
+                    }
+                    const uint32_t above = suf - s;          // keys with a larger digit than this lane's bins
+                    if (above < krem && krem <= above + s) {
+                        uint32_t cum = above;
+                        int d;
+                        if (cum + h3 >= krem) d = 3;
+                        else { cum += h3; if (cum + h2 >= krem) d = 2;
+                        else { cum += h2; if (cum + h1 >= krem) d = 1;
+                        else { cum += h1; d = 0; } } }
+                        s_prefix = (prefix << 8) | static_cast<uint32_t>(4 * tid + d);
+                        s_krem = krem - cum;
+                    }
+                }
+                __syncthreads();
+                prefix = s_prefix;
+                krem = s_krem;
+                __syncthreads();
+            }
+            kth = prefix;
+            need_eq = krem;
+        }
+    } else {
+        kth = order_key(a.z_thr);
+        need_eq = 0x7fffffffu;
+    }
+
+    uint32_t base_gt = 0u, base_eq = 0u;
+    for (int c0 = 0; c0 < T; c0 += kSelThreads) {
+        const int t = c0 + tid;
+        uint32_t gt = 0u, eq = 0u;
+        if (t < T) {
+            const uint32_t key = order_key(a.z[t]);
+            gt = key > kth ? 1u : 0u;
+            eq = key == kth ? 1u : 0u;
+        }
+        const uint32_t packed = gt | (eq << 16);
+        uint32_t total;
+        const uint32_t excl = block_scan_inclusive(packed, wsum, total) - packed;
+        const uint32_t gt_before = base_gt + (excl & 0xffffu);
+        const uint32_t eq_before = base_eq + (excl >> 16);
+        if (gt || (eq && eq_before < need_eq)) {
+            const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+            a.idx[pos] = t;
+            if (a.idx_copy) a.idx_copy[pos] = t;
+        }
+        base_gt += total & 0xffffu;
+        base_eq += total >> 16;
+    }
+    const int count = static_cast<int>(base_gt + (base_eq < need_eq ? base_eq : need_eq));
+    if (tid == 0) {
+        *a.count = count;
+        if (a.count_copy) *a.count_copy = count;
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // executed tokens before each sequence boundary: lower_bound(idx, seq_offsets[b])
+    auto lower_bound_idx = [&](int v) {
+        int lo = 0, hi = count;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (a.idx[mid] < v) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    for (int b = tid; b <= a.B; b += kSelThreads) {
+        const int cb = lower_bound_idx(a.seq_offsets[b]);
+        if (a.cu_exec) a.cu_exec[b] = cb;
+        if (a.kv_len && b < a.B) {
+            const int cn = lower_bound_idx(a.seq_offsets[b + 1]);
+            const int old = a.kv_len[b];
+            a.kv_old[b] = old;
+            a.kv_len[b] = old + (cn - cb);
+        }
+    }
+    if (a.row_seq) {
+        for (int i = tid; i < count; i += kSelThreads) {
+            const int t = a.idx[i];
+            int lo = 0, hi = a.B;                           // last b with seq_offsets[b] <= t
+            while (lo + 1 < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (a.seq_offsets[mid] <= t) lo = mid; else hi = mid;
+            }
+            a.row_seq[i] = lo;
+        }
+    }
+}
+
+hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
+    hipLaunchKernelGGL(select_compact_kernel, dim3(1), dim3(kSelThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace qtale

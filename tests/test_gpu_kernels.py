@@ -1,0 +1,131 @@
+"""GPU parity of the individual steps against the CPU oracle, through the C ABI (run with -m gpu).
+
+Bit-exact: packed int4 codes, fp16 scales/zero-points, router scores, selected indices and counts.
+Floating point (W4A16 GEMMs): |gpu - oracle| <= 2e-2 * max(|oracle|, rms(oracle row))."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import qtale_oracle as orc
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def qt():
+    import paper_2602_10431_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def _w(N, K, seed, std=0.02):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(N, K, generator=g) * std
+
+
+@pytest.mark.parametrize("N,K,G", [(256, 256, 32), (256, 688, 32), (688, 256, 32), (100, 136, 64),
+                                   (512, 1024, 128), (33, 4096, 128), (4096, 264, 128)])
+def test_quantize_is_bit_exact(qt, N, K, G):
+    W = _w(N, K, N * 7 + K)
+    W[0, : min(K, G)] = 0.0                                     # a constant-zero group
+    W[1, : min(K, G)] = W[1, : min(K, G)].abs() + 1e-3          # an all-positive group
+    ql = qt.qtale_quantize(W.cuda(), 4, G)
+    torch.cuda.synchronize()
+    codes, s, z = orc.quantize_rtn(W.numpy(), 4, G)
+    assert np.array_equal(ql.codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes))
+    assert np.array_equal(ql.scales.cpu().numpy().view(np.uint16), s.view(np.uint16))
+    assert np.array_equal(ql.zeros.cpu().numpy().view(np.uint16), z.view(np.uint16))
+
+
+def test_quantize_rejects_bad_parameters(qt):
+    W = _w(8, 64, 0).cuda()
+    for bits, group in [(3, 128), (4, 48), (8, 128)]:
+        with pytest.raises(qt.QtaleError):
+            qt.qtale_quantize(W, bits, group)
+    with pytest.raises(qt.QtaleError):
+        qt.qtale_quantize(_w(8, 60, 0).cuda(), 4, 32)           # K % 8 != 0
+
+
+@pytest.mark.parametrize("M,N,K,G", [(64, 256, 256, 32), (32, 256, 688, 32), (7, 688, 256, 32), (300, 416, 512, 128),
+                                     (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128)])
+def test_linear_w4a16_matches_oracle(qt, M, N, K, G):
+    W = _w(N, K, M + N + K)
+    A = torch.randn(M, K, generator=torch.Generator().manual_seed(M)).to(torch.float16)
+    ql = qt.qtale_quantize(W.cuda(), 4, G)
+    out = qt.qtale_linear_w4a16(ql, A.cuda())
+    torch.cuda.synchronize()
+    codes, s, z = orc.quantize_rtn(W.numpy(), 4, G)
+    want = A.to(torch.float64).numpy() @ orc.dequantize(codes, s, z, G).T
+    assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
+
+
+@pytest.mark.parametrize("M,I,K,G", [(64, 688, 256, 32), (200, 352, 512, 128), (5, 64, 128, 64)])
+def test_swiglu_w4a16_matches_oracle(qt, M, I, K, G):
+    Wg, Wu = _w(I, K, 1, 0.05), _w(I, K, 2, 0.05)
+    A = torch.randn(M, K, generator=torch.Generator().manual_seed(3)).to(torch.float16)
+    qg, qu = qt.qtale_quantize(Wg.cuda(), 4, G), qt.qtale_quantize(Wu.cuda(), 4, G)
+    out = qt.qtale_swiglu_w4a16(qg, qu, A.cuda())
+    torch.cuda.synchronize()
+    A64 = A.to(torch.float64).numpy()
+    dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), 4, G), G)
+    du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), 4, G), G)
+    want = orc.silu(A64 @ dg.T) * (A64 @ du.T)
+    assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
+
+
+@pytest.mark.parametrize("T,H,dtype", [(64, 256, "fp16"), (1000, 512, "bf16"), (1, 64, "fp16"), (5000, 256, "bf16"),
+                                       (1025, 4096, "bf16")])
+def test_router_and_selection_are_bit_exact(qt, T, H, dtype):
+    shape = si.LayerShape(H, 4, 4, 64, 256, 4, 32, dtype)
+    x = si.hidden_states(shape, T, T)
+    w = si.router_weight(shape, 0, T)
+    z_ref = orc.router_scores(x.to(torch.float64).numpy(), w.numpy(), 0.125)
+    ctx = qt.Context()
+    lens = [T // 3, T - T // 3 - T // 5, T // 5] if T >= 5 else [T]
+    offs, _ = si.ragged_sequences(lens)
+    for mode, val in [("ratio", 0.0), ("ratio", 0.3), ("ratio", 0.5), ("ratio", 1.0), ("threshold", 0.5),
+                      ("threshold", 0.2), ("threshold", 0.0), ("threshold", 1.0)]:
+        if mode == "ratio":
+            qt.qtale_set_exec_ratio(ctx, val)
+            want = orc.select_ratio(z_ref, val)
+        else:
+            qt.qtale_set_threshold(ctx, val)
+            want = orc.select_threshold(z_ref, val)
+        z, idx, cnt, cu = qt.qtale_router_select(ctx, x.cuda(), w.cuda(), 0.125, offs.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(z.cpu().numpy().view(np.uint32), z_ref.view(np.uint32))
+        k = int(cnt.item())
+        assert k == len(want), (mode, val)
+        assert np.array_equal(idx[:k].cpu().numpy(), want)
+        cu_ref = np.searchsorted(want, offs.numpy(), side="left")
+        assert np.array_equal(cu.cpu().numpy(), cu_ref)
+
+
+def test_selection_ties_go_to_lower_index(qt):
+    # identical rows give identical scores: ties must be resolved by token index
+    shape = si.LayerShape(64, 1, 1, 64, 64, 4, 32, "fp16")
+    base = si.hidden_states(shape, 4, 1)
+    x = base[[0, 1, 0, 0, 2, 0, 3, 0, 0]].contiguous()           # five copies of row 0
+    w = si.router_weight(shape, 0, 2)
+    z_ref = orc.router_scores(x.to(torch.float64).numpy(), w.numpy(), 0.0)
+    ctx = qt.Context()
+    for r in [0.2, 0.34, 0.5, 0.67, 0.9]:
+        qt.qtale_set_exec_ratio(ctx, r)
+        z, idx, cnt, _ = qt.qtale_router_select(ctx, x.cuda(), w.cuda(), 0.0)
+        torch.cuda.synchronize()
+        want = orc.select_ratio(z_ref, r)
+        assert int(cnt.item()) == len(want) and np.array_equal(idx[: len(want)].cpu().numpy(), want)
+
+
+def test_selection_is_deterministic(qt):
+    shape = si.LayerShape(256, 4, 4, 64, 256, 4, 32, "bf16")
+    x = si.hidden_states(shape, 3000, 9).cuda()
+    w = si.router_weight(shape, 0, 9).cuda()
+    ctx = qt.Context()
+    qt.qtale_set_exec_ratio(ctx, 0.37)
+    a = qt.qtale_router_select(ctx, x, w)
+    b = qt.qtale_router_select(ctx, x, w)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
