@@ -80,6 +80,7 @@ def quantize_rtn(W, bits=4, group=128):
         s16[bad] = np.float16(1.0)
         sf = s16.astype(np.float32)
         z = np.clip(np.rint((-lo / sf).astype(np.float32)), 0, qmax).astype(np.float32)
+        z = z + np.float32(0.0)          # the zero-point is an integer code: -0.0 (from lo == 0) is stored as +0
         q = np.rint((Wg / sf[:, None]).astype(np.float32)).astype(np.float32) + z[:, None]
         q = np.clip(q, 0, qmax)
         codes[:, k0:k1] = q.astype(np.uint8)

@@ -128,3 +128,9 @@ def test_packed_size_matches_shape_arithmetic():
     P = si.C2.params_per_layer()
     assert P == 202375168
     assert P // 2 + 2 * 2 * (P // 128) == 101187584 + 6324224
+
+
+def test_zero_point_is_never_negative_zero():
+    W = np.abs(_rand_w(4, 64, 33)) + 0.01                        # lo = 0 -> -lo/s = -0.0
+    _, _, z = orc.quantize_rtn(W, 4, 32)
+    assert np.all(z.view(np.uint16) == 0)
