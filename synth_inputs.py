@@ -58,8 +58,8 @@ _SLOTS = {"q": 0, "k": 1, "v": 2, "o": 3, "gate": 4, "up": 5, "down": 6,
           "x_step": 13, "misc": 14}
 
 
-def _gen(seed, layer, slot, extra=0):
-    g = torch.Generator(device="cpu")
+def _gen(seed, layer, slot, extra=0, device="cpu"):
+    g = torch.Generator(device=device)
     g.manual_seed((int(seed) * 1000003 + int(layer) * 1009 + _SLOTS[slot] * 17 + int(extra) * 7919) % (2 ** 62))
     return g
 
@@ -68,16 +68,19 @@ def torch_dtype(name):
     return {"fp16": torch.float16, "bf16": torch.bfloat16}[name]
 
 
-def linear_weight(shape: LayerShape, name, layer, seed, std=0.02):
-    """fp32 [N, K] weight of one linear, N(0, std)."""
+def linear_weight(shape: LayerShape, name, layer, seed, std=0.02, device="cpu"):
+    """fp32 [N, K] weight of one linear, N(0, std).  device="cuda" draws on the GPU (same
+    distribution, different bits than the CPU generator); parity tests always use the CPU."""
     for nm, n, k in shape.linear_shapes():
         if nm == name:
-            return torch.randn(n, k, generator=_gen(seed, layer, name), dtype=torch.float32) * std
+            return torch.randn(n, k, generator=_gen(seed, layer, name, device=device), dtype=torch.float32,
+                               device=device) * std
     raise KeyError(name)
 
 
-def router_weight(shape: LayerShape, layer, seed, std=0.02):
-    return torch.randn(shape.hidden, generator=_gen(seed, layer, "router_w"), dtype=torch.float32) * std
+def router_weight(shape: LayerShape, layer, seed, std=0.02, device="cpu"):
+    return torch.randn(shape.hidden, generator=_gen(seed, layer, "router_w", device=device), dtype=torch.float32,
+                       device=device) * std
 
 
 def norm_gains(shape: LayerShape, layer, seed, unit=True):
@@ -90,18 +93,18 @@ def norm_gains(shape: LayerShape, layer, seed, unit=True):
     return g1.to(dt), g2.to(dt)
 
 
-def layer_tensors(shape: LayerShape, layer, seed, unit_gains=True, std=0.02):
+def layer_tensors(shape: LayerShape, layer, seed, unit_gains=True, std=0.02, device="cpu"):
     """All fp32 weights of one layer plus router and gains, as a dict."""
-    out = {nm: linear_weight(shape, nm, layer, seed, std) for nm, _, _ in shape.linear_shapes()}
-    out["router_w"] = router_weight(shape, layer, seed, std)
+    out = {nm: linear_weight(shape, nm, layer, seed, std, device) for nm, _, _ in shape.linear_shapes()}
+    out["router_w"] = router_weight(shape, layer, seed, std, device)
     out["router_b"] = 0.0
     out["g1"], out["g2"] = norm_gains(shape, layer, seed, unit_gains)
     return out
 
 
-def hidden_states(shape: LayerShape, T, seed, slot="x", extra=0):
+def hidden_states(shape: LayerShape, T, seed, slot="x", extra=0, device="cpu"):
     """[T, hidden] ~ N(0,1) rounded to the activation dtype."""
-    x = torch.randn(T, shape.hidden, generator=_gen(seed, 0, slot, extra), dtype=torch.float32)
+    x = torch.randn(T, shape.hidden, generator=_gen(seed, 0, slot, extra, device), dtype=torch.float32, device=device)
     return x.to(torch_dtype(shape.act_dtype))
 
 
