@@ -76,7 +76,8 @@ int qtale_get_control(const qtale_ctx* ctx, int* mode /*host*/, float* value /*h
  *   zeros     [N][ceil(K/group)] fp16 bit patterns of the integer zero-point
  *   prepacked the kernels' private copy (codes reordered for the matrix-core operand layout plus
  *             scale/zero pairs), qtale_prepacked_bytes() bytes, 16-byte aligned; may be NULL here.
- * Supported: bits = 4; group in {32, 64, 128}; K % 8 == 0.  Else QTALE_ERR_UNSUPPORTED / _SHAPE. */
+ * Supported: bits = 4; group in {32, 64, 128}; K % 8 == 0.  Else QTALE_ERR_UNSUPPORTED / _SHAPE.
+ * The GEMM entry points (forward calls, qtale_linear_w4a16, qtale_swiglu_w4a16) also need N % 8 == 0. */
 size_t qtale_prepacked_bytes(int N, int K, int bits, int group);
 int qtale_quantize(const float* W, int N, int K, int bits, int group,
                    uint32_t* codes, uint16_t* scales, uint16_t* zeros,

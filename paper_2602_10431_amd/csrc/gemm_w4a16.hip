@@ -13,6 +13,8 @@
 //     before the current tile's MFMAs.
 //   * Epilogues fuse what follows the linear: fp16 store (q|k|v), residual add from the gathered rows
 //     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
+//     The accumulators are transposed through LDS so that every global access is row-contiguous.
+#include <cstdlib>
 #include "qtale_dev.h"
 #include "qtale_kernels.h"
 
@@ -78,7 +80,10 @@ gemm_w4a16_kernel(GemmDev p) {
     static_assert((BM * 8) % NT == 0, "A tile must split evenly over the threads");
     static_assert(EPI != EPI_SWIGLU_F16 || (FN % 2) == 0, "gate/up fragments come in pairs");
 
-    __shared__ __attribute__((aligned(16))) half_t As[2][BM * kLdsStride];
+    constexpr int kABytes = 2 * BM * kLdsStride * 2;
+    constexpr int kCBytes = WM * WN * 32 * ((EPI == EPI_SWIGLU_F16 ? FN / 2 : FN) * 32 + 8) * 4;
+    __shared__ __attribute__((aligned(16))) char smem[kABytes > kCBytes ? kABytes : kCBytes];
+    half_t (*As)[BM * kLdsStride] = reinterpret_cast<half_t (*)[BM * kLdsStride]>(smem);
 
     const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
     const int tile_m = blockIdx.x % p.tiles_m;
@@ -97,13 +102,11 @@ gemm_w4a16_kernel(GemmDev p) {
     // ---- which weight fragments this wave owns --------------------------------------------------
     const U4* bp[FN];
     const uint32_t* sp[FN];
-    int npad[FN], mat_of[FN], frag_of[FN];
-    bool valid[FN];
+    int npad[FN];
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
         int vf = (tile_n * WN + wn) * FN + fn;
-        valid[fn] = vf < p.vf_total;
-        if (!valid[fn]) vf = p.vf_total - 1;
+        if (vf >= p.vf_total) vf = p.vf_total - 1;     // edge tile: recompute the last fragment, never stored
         int mat, f;
         if (EPI == EPI_SWIGLU_F16) {
             mat = vf & 1;
@@ -114,8 +117,6 @@ gemm_w4a16_kernel(GemmDev p) {
             if (p.n_w > 1 && f >= p.NF[0]) { f -= p.NF[0]; mat = 1; }
             if (p.n_w > 2 && mat == 1 && f >= p.NF[1]) { f -= p.NF[1]; mat = 2; }
         }
-        mat_of[fn] = mat;
-        frag_of[fn] = f;
         bp[fn] = p.codes[mat] + static_cast<size_t>(f) * p.KT * 64 + lane;
         sp[fn] = p.sz[mat] + f * 32 + l32;
         npad[fn] = p.npad[mat];
@@ -173,6 +174,9 @@ gemm_w4a16_kernel(GemmDev p) {
     load_a(0);
     load_b(0, bq, szraw);
     store_a(0);
+    // Drain the prologue loads here: a load still pending at the loop header would make the compiler
+    // place its vmcnt wait inside the loop, where it would also wait for the prefetches just issued.
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     __syncthreads();
 
     const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
@@ -217,37 +221,95 @@ gemm_w4a16_kernel(GemmDev p) {
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
-    // accumulator register r of a lane holds C[row][col] with col = lane%32 and
-    // row = 8*(r/4) + 4*(lane/32) + r%4 inside the 32x32 fragment.
+    // Accumulator register r of a lane holds C[row][col] with col = lane%32 and
+    // row = 8*(r/4) + 4*(lane/32) + r%4 inside a 32x32 fragment.  Each wave transposes one 32-row slab at
+    // a time through its private LDS region (the A tiles are dead by now) so that global traffic is
+    // row-contiguous: a lane then owns 4 consecutive columns of one row (16-byte fp32 / 8-byte 16-bit
+    // accesses, 256+ contiguous bytes per row per wave).
+    constexpr int NFO = EPI == EPI_SWIGLU_F16 ? FN / 2 : FN;   // output fragments per wave
+    constexpr int CW = NFO * 32;                               // output columns per wave
+    constexpr int CSTR = CW + 8;                               // slab row stride (floats): conflict-free writes
+    constexpr int LPR = CW / 4;                                // lanes per row when reading back
+    constexpr int RPP = 64 / LPR;                              // rows per pass
+    constexpr int PASSES = 32 / RPP;
+    float* Cs = reinterpret_cast<float*>(smem) + wave * (32 * CSTR);
+    const int rr = lane / LPR;                                 // row inside a pass
+    const int c4 = (lane % LPR) * 4;                           // first of this lane's 4 columns in the slab
+    // which output fragment / matrix the lane's columns belong to
+    const int fo = c4 >> 5;
+    int o_vf = (tile_n * WN + wn) * FN + (EPI == EPI_SWIGLU_F16 ? 2 * fo : fo);
+    const bool o_valid = o_vf < p.vf_total;
+    int o_mat = 0, o_f = o_vf;
+    if (EPI == EPI_SWIGLU_F16) {
+        o_f = o_vf >> 1;
+    } else {
+        if (p.n_w > 1 && o_f >= p.NF[0]) { o_f -= p.NF[0]; o_mat = 1; }
+        if (p.n_w > 2 && o_mat == 1 && o_f >= p.NF[1]) { o_f -= p.NF[1]; o_mat = 2; }
+    }
+    const int o_ncol = o_f * 32 + (c4 & 31);
+    const bool col_ok = o_valid && o_ncol < p.N[o_mat];        // N % 4 == 0: the 4 columns are all in or all out
+    const int col = (EPI == EPI_SWIGLU_F16 ? 0 : p.colbase[o_mat]) + o_ncol;
+    const int32_t* __restrict__ idx = p.idx;
+
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
-        const int rbase = m0 + (wm * FM + fm) * 32 + 4 * lhi;
 #pragma unroll
-        for (int fn = 0; fn < FN; fn += (EPI == EPI_SWIGLU_F16 ? 2 : 1)) {
-            if (!valid[fn]) continue;
-            const int mat = mat_of[fn];
-            const int ncol = frag_of[fn] * 32 + l32;
-            if (ncol >= p.N[mat]) continue;
-            const int col = (EPI == EPI_SWIGLU_F16 ? 0 : p.colbase[mat]) + ncol;
+        for (int f = 0; f < NFO; ++f) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = rbase + 8 * (r >> 2) + (r & 3);
-                if (row >= M) continue;
-                if (EPI == EPI_STORE_F16) {
-                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(row) * p.ldo + col] =
-                        float_to_half_bits(acc[fm][fn][r]);
-                } else if (EPI == EPI_SWIGLU_F16) {
-                    const float v = silu_f(acc[fm][fn][r]) * acc[fm][fn + 1][r];
-                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(row) * p.ldo + col] = float_to_half_bits(v);
+                float v;
+                if (EPI == EPI_SWIGLU_F16) v = silu_f(acc[fm][2 * f][r]) * acc[fm][2 * f + 1][r];
+                else v = acc[fm][f][r];
+                Cs[(8 * (r >> 2) + 4 * lhi + (r & 3)) * CSTR + f * 32 + l32] = v;
+            }
+        }
+        const int row0 = m0 + (wm * FM + fm) * 32 + rr;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ps += 4) {
+            float4 v[4], res[4];
+            uint2 xr[4];
+            int trow[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = row0 + (ps + u) * RPP;
+                ok[u] = col_ok && row < M;
+                v[u] = *reinterpret_cast<const float4*>(&Cs[((ps + u) * RPP + rr) * CSTR + c4]);
+                trow[u] = row;
+                if (EPI == EPI_RESID_F32 || EPI == EPI_RESID_SCATTER) trow[u] = ok[u] ? idx[row] : 0;
+            }
+            if (EPI == EPI_RESID_F32) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) xr[u] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(p.resid) + static_cast<size_t>(trow[u]) * p.ldo + col);
+            } else if (EPI == EPI_RESID_SCATTER) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) res[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.resid) + static_cast<size_t>(row0 + (ps + u) * RPP) * p.ldo + col);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (!ok[u]) continue;
+                const int row = row0 + (ps + u) * RPP;
+                if (EPI == EPI_STORE_F16 || EPI == EPI_SWIGLU_F16) {
+                    uint2 o;
+                    o.x = static_cast<uint32_t>(float_to_half_bits(v[u].x)) | (static_cast<uint32_t>(float_to_half_bits(v[u].y)) << 16);
+                    o.y = static_cast<uint32_t>(float_to_half_bits(v[u].z)) | (static_cast<uint32_t>(float_to_half_bits(v[u].w)) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
                 } else if (EPI == EPI_RESID_F32) {
-                    const int t = p.idx[row];
-                    const float xv = act_to_float(reinterpret_cast<const uint16_t*>(p.resid)[static_cast<size_t>(t) * p.ldo + col], p.bf16);
-                    reinterpret_cast<float*>(p.out)[static_cast<size_t>(row) * p.ldo + col] = xv + acc[fm][fn][r];
+                    float4 o;
+                    o.x = act_to_float(static_cast<uint16_t>(xr[u].x & 0xffffu), p.bf16) + v[u].x;
+                    o.y = act_to_float(static_cast<uint16_t>(xr[u].x >> 16), p.bf16) + v[u].y;
+                    o.z = act_to_float(static_cast<uint16_t>(xr[u].y & 0xffffu), p.bf16) + v[u].z;
+                    o.w = act_to_float(static_cast<uint16_t>(xr[u].y >> 16), p.bf16) + v[u].w;
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
                 } else {
-                    const int t = p.idx[row];
-                    const float hv = reinterpret_cast<const float*>(p.resid)[static_cast<size_t>(row) * p.ldo + col];
-                    reinterpret_cast<uint16_t*>(p.out)[static_cast<size_t>(t) * p.ldo + col] =
-                        float_to_act(hv + acc[fm][fn][r], p.bf16);
+                    uint2 o;
+                    o.x = static_cast<uint32_t>(float_to_act(res[u].x + v[u].x, p.bf16)) |
+                          (static_cast<uint32_t>(float_to_act(res[u].y + v[u].y, p.bf16)) << 16);
+                    o.y = static_cast<uint32_t>(float_to_act(res[u].z + v[u].z, p.bf16)) |
+                          (static_cast<uint32_t>(float_to_act(res[u].w + v[u].w, p.bf16)) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(trow[u]) * p.ldo + col) = o;
                 }
             }
         }
@@ -269,6 +331,10 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
 template <int GPT, int EPI>
 static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
     if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI>(d, stream);
+    static const int cfgsel = getenv("QTALE_GEMM_CFG") ? atoi(getenv("QTALE_GEMM_CFG")) : 1;
+    if (cfgsel == 1) return launch_cfg<2, 4, 4, 2, GPT, EPI>(d, stream);
+    if (cfgsel == 2) return launch_cfg<4, 2, 2, 4, GPT, EPI>(d, stream);
+    if (cfgsel == 3) return launch_cfg<2, 2, 2, 4, GPT, EPI>(d, stream);
     return launch_cfg<2, 2, 4, 4, GPT, EPI>(d, stream);
 }
 

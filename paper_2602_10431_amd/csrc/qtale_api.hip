@@ -97,7 +97,7 @@ int check_cfg(const qtale_layer_cfg* c) {
 
 int check_linear(const qtale_qlinear& l, int N, int K) {
     if (!l.prepacked) return QTALE_ERR_INVALID_ARG;
-    if (l.N != N || l.K != K) return QTALE_ERR_SHAPE;
+    if (l.N != N || l.K != K || N % 8 != 0) return QTALE_ERR_SHAPE;
     return QTALE_OK;
 }
 
@@ -437,6 +437,7 @@ int qtale_linear_w4a16(const qtale_qlinear* w, int group, const void* A, int M, 
     if (!w || M < 0) return QTALE_ERR_INVALID_ARG;
     int e = check_quant_params(w->N, w->K, 4, group);
     if (e) return e;
+    if (w->N % 8 != 0) return QTALE_ERR_SHAPE;
     if (M == 0) return QTALE_OK;
     if (!w->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
@@ -452,7 +453,7 @@ int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int g
     if (!gate || !up || M < 0) return QTALE_ERR_INVALID_ARG;
     int e = check_quant_params(gate->N, gate->K, 4, group);
     if (e) return e;
-    if (gate->N != up->N || gate->K != up->K) return QTALE_ERR_SHAPE;
+    if (gate->N != up->N || gate->K != up->K || gate->N % 8 != 0) return QTALE_ERR_SHAPE;
     if (M == 0) return QTALE_OK;
     if (!gate->prepacked || !up->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
