@@ -71,8 +71,8 @@ __device__ __forceinline__ ScaleZero expand_sz(uint32_t raw) {
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int WM, int WN, int FM, int FN, int GPT, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64)
+template <int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED>
+__global__ void __launch_bounds__(WM * WN * 64, OCC)
 gemm_w4a16_kernel(GemmDev p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * FM * 32;
@@ -93,15 +93,15 @@ gemm_w4a16_kernel(GemmDev p) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: lives in an SGPR
     const int wm = wave % WM;
     const int wn = wave / WM;
     const int l32 = lane & 31;
     const int lhi = lane >> 5;
 
-    // ---- which weight fragments this wave owns --------------------------------------------------
-    const U4* bp[FN];
-    const uint32_t* sp[FN];
+    // ---- which weight fragments this wave owns (all wave-uniform -> scalar base addresses) ------
+    const u32x4_t* bbase[FN];
+    const uint32_t* sbase[FN];
     int npad[FN];
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
@@ -117,8 +117,8 @@ gemm_w4a16_kernel(GemmDev p) {
             if (p.n_w > 1 && f >= p.NF[0]) { f -= p.NF[0]; mat = 1; }
             if (p.n_w > 2 && mat == 1 && f >= p.NF[1]) { f -= p.NF[1]; mat = 2; }
         }
-        bp[fn] = p.codes[mat] + static_cast<size_t>(f) * p.KT * 64 + lane;
-        sp[fn] = p.sz[mat] + f * 32 + l32;
+        bbase[fn] = reinterpret_cast<const u32x4_t*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * 64;
+        sbase[fn] = p.sz[mat] + f * 32;
         npad[fn] = p.npad[mat];
     }
 
@@ -131,93 +131,122 @@ gemm_w4a16_kernel(GemmDev p) {
             for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.0f;
 
     // ---- A tile: global -> registers -> LDS ------------------------------------------------------
-    U4 areg[A_LOADS];
-    const half_t* a_src[A_LOADS];
-    int a_dst[A_LOADS], a_col[A_LOADS];
+    // Every global address is (uniform base advanced per k-tile) + (per-lane offset fixed for the whole
+    // kernel).  When K is not a multiple of 64 (RAGGED) the chunks of the last tile that start at or
+    // beyond K are redirected to the row's last valid chunk: the weights there dequantize to exactly 0
+    // (prepack pads with the zero-point), so any finite activation contributes nothing.
+    u32x4_t areg[A_LOADS];
+    uint32_t a_off[A_LOADS];        // element offset of this thread's chunk inside A (rows clamped to M-1)
+    int a_dst[A_LOADS];
 #pragma unroll
     for (int it = 0; it < A_LOADS; ++it) {
         const int c = it * NT + tid;
         const int row = c >> 3, col8 = c & 7;
         const int gr = min(m0 + row, M - 1);
-        a_src[it] = p.A + static_cast<size_t>(gr) * p.K + col8 * 8;
+        a_off[it] = static_cast<uint32_t>(gr) * static_cast<uint32_t>(p.K) + col8 * 8;
         a_dst[it] = row * kLdsStride + col8 * 8;
-        a_col[it] = col8 * 8;
+    }
+    uint32_t a_adj = 0;             // RAGGED: how far this thread's chunk overshoots K in the last tile
+    if (RAGGED) {
+        const int col = (p.KT - 1) * 64 + (tid & 7) * 8;      // NT % 8 == 0: same column chunk for every `it`
+        a_adj = col >= p.K ? static_cast<uint32_t>(col - (p.K - 8)) : 0u;
     }
     auto load_a = [&](int kt) {
+        const half_t* base = p.A + kt * 64;
+        const uint32_t d = (RAGGED && kt == p.KT - 1) ? a_adj : 0u;
 #pragma unroll
-        for (int it = 0; it < A_LOADS; ++it) {
-            if (kt * 64 + a_col[it] < p.K)
-                areg[it] = *reinterpret_cast<const U4*>(a_src[it] + kt * 64);
-            else
-                areg[it] = U4{0u, 0u, 0u, 0u};
-        }
+        for (int it = 0; it < A_LOADS; ++it) areg[it] = *reinterpret_cast<const u32x4_t*>(base + (a_off[it] - d));
     };
     auto store_a = [&](int buf) {
 #pragma unroll
-        for (int it = 0; it < A_LOADS; ++it) *reinterpret_cast<U4*>(&As[buf][a_dst[it]]) = areg[it];
+        for (int it = 0; it < A_LOADS; ++it) *reinterpret_cast<u32x4_t*>(&As[buf][a_dst[it]]) = areg[it];
     };
 
-    U4 bq[FN], bq_next[FN];
-    uint32_t szraw[FN][GPT], szraw_next[FN][GPT];
-    auto load_b = [&](int kt, U4* dst, uint32_t (*sz)[GPT]) {
+    u32x4_t bq[2][FN];                   // packed codes of the current / next k-tile (ping-pong)
+    uint32_t bsz[2][FN][GPT];       // their scale|zero words
+    auto load_b = [&](int kt, u32x4_t* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) {
-            dst[fn] = bp[fn][static_cast<size_t>(kt) * 64];
+            q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
 #pragma unroll
             for (int g = 0; g < GPT; ++g) {
                 const int gi = (kt * 64 + g * 32) >> p.gshift;
-                sz[fn][g] = sp[fn][static_cast<size_t>(gi) * npad[fn]];
+                sz[fn][g] = (sbase[fn] + static_cast<size_t>(gi) * npad[fn])[l32];
             }
         }
     };
 
+    const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
+
+    // One k-tile: prefetch tile kt+1 (A into registers, B into `nxt`), run the 4 k-steps of tile kt from
+    // its LDS buffer and the codes in `cur`, then park the prefetched A tile in the other LDS buffer.
+    // Inside the tile the A fragments of k-step j+1 are read and the next weight fragment is dequantized
+    // while the matrix core works on the current one; the sched_group_barrier sequence asks for a
+    // "1 MFMA, a few VALU" interleaving.  (On gfx950 an MFMA blocks its own wave's issue for most of its
+    // 8 passes, so the real overlap comes from the second workgroup resident on the same SIMDs.)
     load_a(0);
-    load_b(0, bq, szraw);
+    load_b(0, bq[0], bsz[0]);
     store_a(0);
     // Drain the prologue loads here: a load still pending at the loop header would make the compiler
     // place its vmcnt wait inside the loop, where it would also wait for the prefetches just issued.
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     __syncthreads();
 
-    const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
-    for (int kt = 0; kt < p.KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < p.KT;
-        if (more) {
-            load_a(kt + 1);
-            load_b(kt + 1, bq_next, szraw_next);
-        }
-        ScaleZero sz[FN][GPT];
+    for (int kt0 = 0; kt0 < p.KT; kt0 += 2) {    // unrolled by two: LDS buffer and B registers ping-pong
 #pragma unroll
-        for (int fn = 0; fn < FN; ++fn)
+        for (int h = 0; h < 2; ++h) {
+            const int kt = kt0 + h;
+            if (kt < p.KT) {
+            const bool more = kt + 1 < p.KT;
+            if (more) {
+                load_a(kt + 1);
+                load_b(kt + 1, bq[h ^ 1], bsz[h ^ 1]);
+            }
+            ScaleZero sz[FN][GPT];
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(szraw[fn][g]);
+            for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            half8_t a[FM];
+                for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(bsz[h][fn][g]);
+            auto wsel = [&](int fn, int j) {
+                return j == 0 ? bq[h][fn].x : j == 1 ? bq[h][fn].y : j == 2 ? bq[h][fn].z : bq[h][fn].w;
+            };
+            const half_t* Ab = &As[h][a_row0];
+            half8_t a[2][FM];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm)
-                a[fm] = *reinterpret_cast<const half8_t*>(&As[cur][a_row0 + fm * 32 * kLdsStride + j * 16]);
+            for (int fm = 0; fm < FM; ++fm) a[0][fm] = *reinterpret_cast<const half8_t*>(Ab + fm * 32 * kLdsStride);
+            half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi);
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn) {
-                const uint32_t wj = j == 0 ? bq[fn].x : j == 1 ? bq[fn].y : j == 2 ? bq[fn].z : bq[fn].w;
-                const ScaleZero& s = sz[fn][GPT == 2 ? (j >> 1) : 0];
-                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
+            for (int j = 0; j < 4; ++j) {
+                if (j + 1 < 4) {
 #pragma unroll
-                for (int fm = 0; fm < FM; ++fm)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fm], b, acc[fm][fn], 0, 0, 0);
+                    for (int fm = 0; fm < FM; ++fm)
+                        a[(j + 1) & 1][fm] = *reinterpret_cast<const half8_t*>(Ab + fm * 32 * kLdsStride + (j + 1) * 16);
+                }
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) {
+                    const int fnn = fn + 1 < FN ? fn + 1 : 0;
+                    const int jn = fn + 1 < FN ? j : j + 1;
+                    half8_t bnext = bcur;
+                    if (jn < 4) {
+                        const ScaleZero& sn = sz[fnn][GPT == 2 ? (jn >> 1) : 0];
+                        bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi);
+                    }
+#pragma unroll
+                    for (int fm = 0; fm < FM; ++fm)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j & 1][fm], bcur, acc[fm][fn], 0, 0, 0);
+                    bcur = bnext;
+#pragma unroll
+                    for (int fm = 0; fm < FM; ++fm) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, (13 + FM - 1) / FM, 0);  // its share of the dequant VALU
+                        if (fn == 0 && j + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    }
+                }
+            }
+            if (more) store_a(h ^ 1);
+            __syncthreads();
             }
         }
-        if (more) {
-            store_a(cur ^ 1);
-#pragma unroll
-            for (int fn = 0; fn < FN; ++fn) {
-                bq[fn] = bq_next[fn];
-#pragma unroll
-                for (int g = 0; g < GPT; ++g) szraw[fn][g] = szraw_next[fn][g];
-            }
-        }
-        __syncthreads();
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
@@ -316,7 +345,7 @@ gemm_w4a16_kernel(GemmDev p) {
     }
 }
 
-template <int WM, int WN, int FM, int FN, int GPT, int EPI>
+template <int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC>
 static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     constexpr int BM = WM * FM * 32;
     constexpr int BNF = WN * FN;
@@ -324,18 +353,19 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     d.tiles_n = (d.vf_total + BNF - 1) / BNF;
     const int blocks = d.tiles_m * d.tiles_n;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+    if (d.K % 64 != 0)
+        hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI, OCC, true>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+    else
+        hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI, OCC, false>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
     return hipGetLastError();
 }
 
 template <int GPT, int EPI>
 static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
-    if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI>(d, stream);
-    static const int cfgsel = getenv("QTALE_GEMM_CFG") ? atoi(getenv("QTALE_GEMM_CFG")) : 1;
-    if (cfgsel == 1) return launch_cfg<2, 4, 4, 2, GPT, EPI>(d, stream);
-    if (cfgsel == 2) return launch_cfg<4, 2, 2, 4, GPT, EPI>(d, stream);
-    if (cfgsel == 3) return launch_cfg<2, 2, 2, 4, GPT, EPI>(d, stream);
-    return launch_cfg<2, 2, 4, 4, GPT, EPI>(d, stream);
+    if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI, 2>(d, stream);
+    static const int cfgsel = getenv("QTALE_GEMM_CFG") ? atoi(getenv("QTALE_GEMM_CFG")) : 3;
+    if (cfgsel == 2) return launch_cfg<1, 4, 8, 2, GPT, EPI, 1>(d, stream);
+    return launch_cfg<1, 4, 4, 2, GPT, EPI, 2>(d, stream);
 }
 
 template <int GPT>
