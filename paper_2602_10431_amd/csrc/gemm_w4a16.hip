@@ -9,12 +9,13 @@
 //     nibble position) or 1024 + 16 c (next position); (1024+c) - (1024+z) and (1024+16c)/16 - (64+z)
 //     are exact, one multiply by the scale rounds once.  13 VALU ops per 8 weights.
 //   * Activations are the A operand, staged global -> VGPR -> LDS (row stride 72 halves: conflict-free
-//     16-byte reads), double buffered, one barrier per k-tile; the next tile's global loads are issued
-//     before the current tile's MFMAs.
+//     16-byte reads) through three LDS buffers with one barrier per k-tile placed in the middle of the
+//     tile, so a wave's MFMA stream never stops at a tile boundary (see the pipeline comment below).
+//   * Workgroup tile 128(M) x 256(N), 4 waves of 128 x 64, two workgroups resident per CU: the second
+//     workgroup's waves fill the issue slots a wave loses while its own MFMA is in flight.
 //   * Epilogues fuse what follows the linear: fp16 store (q|k|v), residual add from the gathered rows
 //     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
 //     The accumulators are transposed through LDS so that every global access is row-contiguous.
-#include <cstdlib>
 #include "qtale_dev.h"
 #include "qtale_kernels.h"
 
@@ -80,7 +81,8 @@ gemm_w4a16_kernel(GemmDev p) {
     static_assert((BM * 8) % NT == 0, "A tile must split evenly over the threads");
     static_assert(EPI != EPI_SWIGLU_F16 || (FN % 2) == 0, "gate/up fragments come in pairs");
 
-    constexpr int kABytes = 2 * BM * kLdsStride * 2;
+    constexpr int NBUF = 3;                                     // LDS buffers of the A tile
+    constexpr int kABytes = NBUF * BM * kLdsStride * 2;
     constexpr int kCBytes = WM * WN * 32 * ((EPI == EPI_SWIGLU_F16 ? FN / 2 : FN) * 32 + 8) * 4;
     __shared__ __attribute__((aligned(16))) char smem[kABytes > kCBytes ? kABytes : kCBytes];
     half_t (*As)[BM * kLdsStride] = reinterpret_cast<half_t (*)[BM * kLdsStride]>(smem);
@@ -178,76 +180,82 @@ gemm_w4a16_kernel(GemmDev p) {
 
     const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
 
-    // One k-tile: prefetch tile kt+1 (A into registers, B into `nxt`), run the 4 k-steps of tile kt from
-    // its LDS buffer and the codes in `cur`, then park the prefetched A tile in the other LDS buffer.
-    // Inside the tile the A fragments of k-step j+1 are read and the next weight fragment is dequantized
-    // while the matrix core works on the current one; the sched_group_barrier sequence asks for a
-    // "1 MFMA, a few VALU" interleaving.  (On gfx950 an MFMA blocks its own wave's issue for most of its
-    // 8 passes, so the real overlap comes from the second workgroup resident on the same SIMDs.)
+    // Pipeline (per wave, MFMAs never stop at a tile boundary):
+    //   tile t is computed from LDS buffer t%3 and the codes in bq[0] (bq[1] receives tile t+1);
+    //   start of tile t : issue the B loads of tile t+1;
+    //   after k-step 0  : park the A registers of tile t+1 (loaded one tile ago) in buffer (t+1)%3, issue
+    //                     the A loads of tile t+2, barrier (buffer (t+1)%3 becomes visible; three buffers
+    //                     make the write safe against waves still reading tile t-1);
+    //   during k-step 3 : the first A fragments of tile t+1 are already read from LDS.
+    // Inside a tile the A fragments of the next k-step are read and the next weight fragment is
+    // dequantized while the matrix core works on the current one.  On gfx950 an MFMA blocks its own
+    // wave's issue for most of its 8 passes, so the dequant VALU mostly overlaps with the MFMAs of the
+    // second workgroup resident on the same SIMDs.
+    // The loop body is branch-free: loads past the last tile are clamped to the last tile (redundant but
+    // harmless, their data is never consumed), so the compiler's wait-count bookkeeping sees one
+    // straight-line order of loads and never has to drain the queue conservatively.
+    const int last = p.KT - 1;
     load_a(0);
     load_b(0, bq[0], bsz[0]);
     store_a(0);
     // Drain the prologue loads here: a load still pending at the loop header would make the compiler
     // place its vmcnt wait inside the loop, where it would also wait for the prefetches just issued.
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+    load_a(min(1, last));
     __syncthreads();
 
-    for (int kt0 = 0; kt0 < p.KT; kt0 += 2) {    // unrolled by two: LDS buffer and B registers ping-pong
+    half8_t a[2][FM];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int kt = kt0 + h;
-            if (kt < p.KT) {
-            const bool more = kt + 1 < p.KT;
-            if (more) {
-                load_a(kt + 1);
-                load_b(kt + 1, bq[h ^ 1], bsz[h ^ 1]);
+    for (int fm = 0; fm < FM; ++fm) a[0][fm] = *reinterpret_cast<const half8_t*>(&As[0][a_row0 + fm * 32 * kLdsStride]);
+    int buf = 0;
+    for (int kt = 0; kt < p.KT; ++kt) {
+        const int nbuf = buf == NBUF - 1 ? 0 : buf + 1;
+        load_b(min(kt + 1, last), bq[1], bsz[1]);
+        ScaleZero sz[FN][GPT];
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(bsz[0][fn][g]);
+        auto wsel = [&](int fn, int j) {
+            return j == 0 ? bq[0][fn].x : j == 1 ? bq[0][fn].y : j == 2 ? bq[0][fn].z : bq[0][fn].w;
+        };
+        const half_t* Ab = &As[buf][a_row0];
+        const half_t* An = &As[nbuf][a_row0];
+        half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j == 1) {
+                store_a(nbuf);
+                load_a(min(kt + 2, last));
+                __syncthreads();
             }
-            ScaleZero sz[FN][GPT];
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn)
+            for (int fm = 0; fm < FM; ++fm)
+                a[(j + 1) & 1][fm] = *reinterpret_cast<const half8_t*>((j + 1 < 4 ? Ab + (j + 1) * 16 : An) + fm * 32 * kLdsStride);
 #pragma unroll
-                for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(bsz[h][fn][g]);
-            auto wsel = [&](int fn, int j) {
-                return j == 0 ? bq[h][fn].x : j == 1 ? bq[h][fn].y : j == 2 ? bq[h][fn].z : bq[h][fn].w;
-            };
-            const half_t* Ab = &As[h][a_row0];
-            half8_t a[2][FM];
-#pragma unroll
-            for (int fm = 0; fm < FM; ++fm) a[0][fm] = *reinterpret_cast<const half8_t*>(Ab + fm * 32 * kLdsStride);
-            half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (j + 1 < 4) {
-#pragma unroll
-                    for (int fm = 0; fm < FM; ++fm)
-                        a[(j + 1) & 1][fm] = *reinterpret_cast<const half8_t*>(Ab + fm * 32 * kLdsStride + (j + 1) * 16);
+            for (int fn = 0; fn < FN; ++fn) {
+                const int fnn = fn + 1 < FN ? fn + 1 : 0;
+                const int jn = fn + 1 < FN ? j : j + 1;
+                half8_t bnext = bcur;
+                if (jn < 4) {
+                    const ScaleZero& sn = sz[fnn][GPT == 2 ? (jn >> 1) : 0];
+                    bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi);
                 }
 #pragma unroll
-                for (int fn = 0; fn < FN; ++fn) {
-                    const int fnn = fn + 1 < FN ? fn + 1 : 0;
-                    const int jn = fn + 1 < FN ? j : j + 1;
-                    half8_t bnext = bcur;
-                    if (jn < 4) {
-                        const ScaleZero& sn = sz[fnn][GPT == 2 ? (jn >> 1) : 0];
-                        bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi);
-                    }
-#pragma unroll
-                    for (int fm = 0; fm < FM; ++fm)
-                        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j & 1][fm], bcur, acc[fm][fn], 0, 0, 0);
-                    bcur = bnext;
-#pragma unroll
-                    for (int fm = 0; fm < FM; ++fm) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x002, (13 + FM - 1) / FM, 0);  // its share of the dequant VALU
-                        if (fn == 0 && j + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                    }
-                }
-            }
-            if (more) store_a(h ^ 1);
-            __syncthreads();
+                for (int fm = 0; fm < FM; ++fm)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j & 1][fm], bcur, acc[fm][fn], 0, 0, 0);
+                bcur = bnext;
             }
         }
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) {
+            bq[0][fn] = bq[1][fn];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) bsz[0][fn][g] = bsz[1][fn][g];
+        }
+        buf = nbuf;
     }
+    __syncthreads();     // every wave is done with the A tiles: the epilogue reuses the LDS
 
     // ---- epilogue -------------------------------------------------------------------------------
     // Accumulator register r of a lane holds C[row][col] with col = lane%32 and
@@ -363,8 +371,6 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
 template <int GPT, int EPI>
 static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
     if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI, 2>(d, stream);
-    static const int cfgsel = getenv("QTALE_GEMM_CFG") ? atoi(getenv("QTALE_GEMM_CFG")) : 3;
-    if (cfgsel == 2) return launch_cfg<1, 4, 8, 2, GPT, EPI, 1>(d, stream);
     return launch_cfg<1, 4, 4, 2, GPT, EPI, 2>(d, stream);
 }
 
