@@ -1,0 +1,242 @@
+// Skinny W4A16 GEMM for decode steps: at most 64 executed rows, so the linears stream their weights once
+// and the question is bandwidth and latency, not matrix-core throughput (Sec. 4.1 weights; the executed
+// rows come from the gather of App. B.2).
+//
+// Shape of the work: C[M<=64][N] = A[M][K] x W'[N][K]^T.  The weights (N*K/2 bytes) dominate; A is at most
+// 64 x K fp16 and stays in L2.  A k-loop with a barrier per 64-wide tile would be latency-bound
+// (K/64 round trips), so here nothing synchronises inside the k-loop:
+//   * a workgroup owns NFB consecutive 32-column fragments and ALL of K; its NW waves split K by
+//     interleaving k-tiles (wave w takes tiles w, w+NW, ...), each wave keeping its own accumulators for
+//     all NFB fragments, so its A registers are reused NFB times;
+//   * per tile a wave issues NFB 16-byte weight loads (1 KB each, contiguous in the prepacked layout),
+//     the scale/zero words and the A fragments straight from global memory in MFMA operand order, two
+//     tiles ahead of use, so ~(2 tiles x (NFB + 8) x 1 KB) are in flight per wave;
+//   * the K-split partial sums meet once, at the end: every wave writes its accumulators as a [64][cols]
+//     fp32 slab into LDS, one barrier, and all threads add the NW slabs in wave order (deterministic)
+//     while applying the same fused epilogues as the prefill kernel with row-contiguous accesses.
+// MF = 1 (M <= 32) halves the A loads and MFMAs.
+#include "gemm_common.h"
+
+namespace qtale {
+
+template <int NFB, int NW, int MF, int GPT, int EPI, bool RAGGED>
+__global__ void __launch_bounds__(NW * 64)
+gemm_skinny_kernel(GemmDev p) {
+    constexpr int NT = NW * 64;
+    constexpr int CW = NFB * 32;                 // accumulator columns per wave
+    constexpr int CSTR = CW + 4;                 // slab row stride (floats)
+    constexpr int ROWS = MF * 32;
+    __shared__ __attribute__((aligned(16))) float slab[NW * ROWS * CSTR];
+
+    const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
+    if (M <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int tile_n = blockIdx.x;
+
+    const u32x4_t* bbase[NFB];
+    const uint32_t* sbase[NFB];
+    int npad[NFB];
+#pragma unroll
+    for (int fn = 0; fn < NFB; ++fn) {
+        int vf = tile_n * NFB + fn;
+        if (vf >= p.vf_total) vf = p.vf_total - 1;
+        int mat, f;
+        map_fragment<EPI>(p, vf, mat, f);
+        bbase[fn] = reinterpret_cast<const u32x4_t*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * 64;
+        sbase[fn] = p.sz[mat] + f * 32;
+        npad[fn] = p.npad[mat];
+    }
+
+    float16_t acc[MF][NFB];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int fn = 0; fn < NFB; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][fn][r] = 0.0f;
+
+    // per-lane A row offsets (rows clamped to M-1: their results are never stored)
+    uint32_t a_off[MF];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+        a_off[mf] = static_cast<uint32_t>(min(mf * 32 + l32, M - 1)) * static_cast<uint32_t>(p.K) + lhi * 8;
+
+    struct Tile {
+        u32x4_t q[NFB];
+        uint32_t sz[NFB][GPT];
+        half8_t a[MF][4];
+    };
+    auto fetch = [&](int kt, Tile& t) {
+#pragma unroll
+        for (int fn = 0; fn < NFB; ++fn) {
+            t.q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) {
+                const int gi = (kt * 64 + g * 32) >> p.gshift;
+                t.sz[fn][g] = (sbase[fn] + static_cast<size_t>(gi) * npad[fn])[l32];
+            }
+        }
+        const half_t* base = p.A + kt * 64;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t shift = 0;
+            if (RAGGED) {                           // chunks starting at or beyond K read the row's last
+                const int col = kt * 64 + j * 16 + lhi * 8;     // valid chunk: the weights there are 0
+                shift = col >= p.K ? static_cast<uint32_t>(col - (p.K - 8)) : 0u;
+            }
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+                t.a[mf][j] = *reinterpret_cast<const half8_t*>(base + (a_off[mf] + j * 16 - shift));
+        }
+    };
+    auto compute = [&](const Tile& t) {
+#pragma unroll
+        for (int fn = 0; fn < NFB; ++fn) {
+            ScaleZero sz[GPT];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) sz[g] = expand_sz(t.sz[fn][g]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t wj = j == 0 ? t.q[fn].x : j == 1 ? t.q[fn].y : j == 2 ? t.q[fn].z : t.q[fn].w;
+                const ScaleZero& s = sz[GPT == 2 ? (j >> 1) : 0];
+                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf)
+                    acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(t.a[mf][j], b, acc[mf][fn], 0, 0, 0);
+            }
+        }
+    };
+
+    // wave w owns tiles w, w + NW, ...  With 8 waves (256 registers each) two tiles are kept in flight;
+    // with 16 waves (128 registers each) one tile, and the four waves per SIMD overlap each other.
+    if (NW <= 8) {
+        Tile t0, t1;
+        int kt = wave;
+        if (kt < p.KT) fetch(kt, t0);
+        if (kt + NW < p.KT) fetch(kt + NW, t1);
+        for (; kt < p.KT; kt += 2 * NW) {
+            compute(t0);
+            if (kt + 2 * NW < p.KT) fetch(kt + 2 * NW, t0);
+            if (kt + NW < p.KT) {
+                compute(t1);
+                if (kt + 3 * NW < p.KT) fetch(kt + 3 * NW, t1);
+            }
+        }
+    } else {
+        Tile t0;
+        for (int kt = wave; kt < p.KT; kt += NW) {
+            fetch(kt, t0);
+            compute(t0);
+        }
+    }
+
+    // ---- meet: slabs into LDS, one barrier, ordered sum + epilogue ----------------------------------
+    float* mine = slab + wave * (ROWS * CSTR);
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int fn = 0; fn < NFB; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                mine[(mf * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3)) * CSTR + fn * 32 + l32] = acc[mf][fn][r];
+    __syncthreads();
+
+    constexpr int NFO = EPI == EPI_SWIGLU_F16 ? NFB / 2 : NFB;   // output fragments of the workgroup
+    constexpr int CWO = NFO * 32;
+    constexpr int LPR = CWO / 4;                                 // lanes per output row (4 columns each)
+    constexpr int RPP = NT / LPR;                                // rows per pass
+    const int c4 = (tid % LPR) * 4;
+    const int fo = c4 >> 5;
+    int o_vf = tile_n * NFB + (EPI == EPI_SWIGLU_F16 ? 2 * fo : fo);
+    const bool o_valid = o_vf < p.vf_total;
+    int o_mat, o_f;
+    map_fragment<EPI>(p, o_valid ? o_vf : p.vf_total - 1, o_mat, o_f);
+    const int o_ncol = o_f * 32 + (c4 & 31);
+    const bool col_ok = o_valid && o_ncol < p.N[o_mat];
+    const int col = (EPI == EPI_SWIGLU_F16 ? 0 : p.colbase[o_mat]) + o_ncol;
+    // slab column of the lane's first value (SwiGLU: gate fragment 2*fo, up fragment 2*fo+1)
+    const int sc = EPI == EPI_SWIGLU_F16 ? (2 * fo) * 32 + (c4 & 31) : c4;
+
+    for (int row = tid / LPR; row < ROWS; row += RPP) {
+        if (!col_ok || row >= M) continue;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f), u = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float* s = slab + w * (ROWS * CSTR) + row * CSTR + sc;
+            const float4 t = *reinterpret_cast<const float4*>(s);
+            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            if (EPI == EPI_SWIGLU_F16) {
+                const float4 t2 = *reinterpret_cast<const float4*>(s + 32);
+                u.x += t2.x; u.y += t2.y; u.z += t2.z; u.w += t2.w;
+            }
+        }
+        if (EPI == EPI_SWIGLU_F16) {
+            v.x = silu_f(v.x) * u.x; v.y = silu_f(v.y) * u.y; v.z = silu_f(v.z) * u.z; v.w = silu_f(v.w) * u.w;
+        }
+        if (EPI == EPI_STORE_F16 || EPI == EPI_SWIGLU_F16) {
+            uint2 o;
+            o.x = static_cast<uint32_t>(float_to_half_bits(v.x)) | (static_cast<uint32_t>(float_to_half_bits(v.y)) << 16);
+            o.y = static_cast<uint32_t>(float_to_half_bits(v.z)) | (static_cast<uint32_t>(float_to_half_bits(v.w)) << 16);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
+        } else if (EPI == EPI_RESID_F32) {
+            const int t = p.idx[row];
+            const uint2 xr = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(p.resid) + static_cast<size_t>(t) * p.ldo + col);
+            float4 o;
+            o.x = act_to_float(static_cast<uint16_t>(xr.x & 0xffffu), p.bf16) + v.x;
+            o.y = act_to_float(static_cast<uint16_t>(xr.x >> 16), p.bf16) + v.y;
+            o.z = act_to_float(static_cast<uint16_t>(xr.y & 0xffffu), p.bf16) + v.z;
+            o.w = act_to_float(static_cast<uint16_t>(xr.y >> 16), p.bf16) + v.w;
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
+        } else {
+            const int t = p.idx[row];
+            const float4 res = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.resid) + static_cast<size_t>(row) * p.ldo + col);
+            uint2 o;
+            o.x = static_cast<uint32_t>(float_to_act(res.x + v.x, p.bf16)) | (static_cast<uint32_t>(float_to_act(res.y + v.y, p.bf16)) << 16);
+            o.y = static_cast<uint32_t>(float_to_act(res.z + v.z, p.bf16)) | (static_cast<uint32_t>(float_to_act(res.w + v.w, p.bf16)) << 16);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(t) * p.ldo + col) = o;
+        }
+    }
+}
+
+template <int NFB, int NW, int MF, int GPT, int EPI>
+static hipError_t launch_one(GemmDev& d, hipStream_t stream) {
+    const int blocks = (d.vf_total + NFB - 1) / NFB;
+    if (blocks == 0) return hipSuccess;
+    if (d.K % 64 != 0)
+        hipLaunchKernelGGL((gemm_skinny_kernel<NFB, NW, MF, GPT, EPI, true>), dim3(blocks), dim3(NW * 64), 0, stream, d);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<NFB, NW, MF, GPT, EPI, false>), dim3(blocks), dim3(NW * 64), 0, stream, d);
+    return hipGetLastError();
+}
+
+template <int GPT, int EPI>
+static hipError_t launch_shape(GemmDev& d, hipStream_t stream) {
+    // SwiGLU needs gate and up fragments side by side; otherwise narrow linears (few fragments) use one
+    // fragment per workgroup and 16 K-slices so that more CUs take part.
+    const bool wide = EPI == EPI_SWIGLU_F16 || d.vf_total >= 256;
+    if (d.M_max <= 32) {
+        if (wide) return launch_one<2, 8, 1, GPT, EPI>(d, stream);
+        return launch_one<(EPI == EPI_SWIGLU_F16 ? 2 : 1), (EPI == EPI_SWIGLU_F16 ? 8 : 16), 1, GPT, EPI>(d, stream);
+    }
+    if (wide) return launch_one<2, 8, 2, GPT, EPI>(d, stream);
+    return launch_one<(EPI == EPI_SWIGLU_F16 ? 2 : 1), (EPI == EPI_SWIGLU_F16 ? 8 : 16), 2, GPT, EPI>(d, stream);
+}
+
+template <int GPT>
+static hipError_t launch_gpt(GemmDev& d, int epi, hipStream_t stream) {
+    switch (epi) {
+        case EPI_STORE_F16: return launch_shape<GPT, EPI_STORE_F16>(d, stream);
+        case EPI_RESID_F32: return launch_shape<GPT, EPI_RESID_F32>(d, stream);
+        case EPI_SWIGLU_F16: return launch_shape<GPT, EPI_SWIGLU_F16>(d, stream);
+        default: return launch_shape<GPT, EPI_RESID_SCATTER>(d, stream);
+    }
+}
+
+hipError_t launch_gemm_skinny(GemmDev& d, int epilogue, hipStream_t stream) {
+    if (d.gshift == 5) return launch_gpt<2>(d, epilogue, stream);
+    return launch_gpt<1>(d, epilogue, stream);
+}
+
+}  // namespace qtale

@@ -16,61 +16,9 @@
 //   * Epilogues fuse what follows the linear: fp16 store (q|k|v), residual add from the gathered rows
 //     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
 //     The accumulators are transposed through LDS so that every global access is row-contiguous.
-#include "qtale_dev.h"
-#include "qtale_kernels.h"
+#include "gemm_common.h"
 
 namespace qtale {
-
-struct GemmDev {
-    const half_t* A;
-    const int32_t* count;
-    int M_max, K, KT, gshift;
-    const U4* codes[3];
-    const uint32_t* sz[3];
-    int N[3], NF[3], npad[3], colbase[3];
-    int n_w, vf_total, tiles_m, tiles_n;
-    void* out;
-    int ldo;
-    const void* resid;
-    const int32_t* idx;
-    int bf16;
-};
-
-constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
-
-__device__ __forceinline__ half8_t dequant8(uint32_t w, half2_t S, half2_t Zlo, half2_t Zhi) {
-    const uint32_t kMagic = 0x64006400u;
-    const half2_t sixteenth = {static_cast<half_t>(0.0625f), static_cast<half_t>(0.0625f)};
-    const uint32_t w8 = w >> 8;
-    const half2_t l0 = __builtin_bit_cast(half2_t, (w & 0x000f000fu) | kMagic);
-    const half2_t h0 = __builtin_bit_cast(half2_t, (w & 0x00f000f0u) | kMagic);
-    const half2_t l1 = __builtin_bit_cast(half2_t, (w8 & 0x000f000fu) | kMagic);
-    const half2_t h1 = __builtin_bit_cast(half2_t, (w8 & 0x00f000f0u) | kMagic);
-    const half2_t p0 = (l0 - Zlo) * S;
-    const half2_t p1 = __builtin_elementwise_fma(h0, sixteenth, -Zhi) * S;
-    const half2_t p2 = (l1 - Zlo) * S;
-    const half2_t p3 = __builtin_elementwise_fma(h1, sixteenth, -Zhi) * S;
-    half8_t r;
-    r[0] = p0[0]; r[1] = p0[1]; r[2] = p1[0]; r[3] = p1[1];
-    r[4] = p2[0]; r[5] = p2[1]; r[6] = p3[0]; r[7] = p3[1];
-    return r;
-}
-
-struct ScaleZero {
-    half2_t S, Zlo, Zhi;
-};
-__device__ __forceinline__ ScaleZero expand_sz(uint32_t raw) {
-    const half2_t sz = __builtin_bit_cast(half2_t, raw);       // [0] = scale, [1] = zero-point
-    ScaleZero r;
-    r.S = half2_t{sz[0], sz[0]};
-    const half_t zlo = sz[1] + static_cast<half_t>(1024.0f);
-    const half_t zhi = sz[1] + static_cast<half_t>(64.0f);
-    r.Zlo = half2_t{zlo, zlo};
-    r.Zhi = half2_t{zhi, zhi};
-    return r;
-}
-
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
 template <int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED>
 __global__ void __launch_bounds__(WM * WN * 64, OCC)
@@ -370,7 +318,6 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
 
 template <int GPT, int EPI>
 static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
-    if (d.M_max <= 64) return launch_cfg<1, 4, 2, 2, GPT, EPI, 2>(d, stream);
     return launch_cfg<1, 4, 4, 2, GPT, EPI, 2>(d, stream);
 }
 
@@ -412,6 +359,7 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     d.resid = a.resid;
     d.idx = a.idx;
     d.bf16 = a.bf16;
+    if (d.M_max <= 64) return launch_gemm_skinny(d, a.epilogue, stream);
     if (a.group == 32) return launch_gpt<2>(d, a.epilogue, stream);
     return launch_gpt<1>(d, a.epilogue, stream);
 }

@@ -114,11 +114,13 @@ hipError_t launch_rmsnorm_f32(const float* h, int H, const int32_t* count, int m
 
 // Rotary embedding, half-split pairing (element i with i + d/2), angle = position * base^(-2i/d), at
 // the ORIGINAL absolute position of the token (a bypassed token leaves a gap in the positions seen by
-// a layer).  One workgroup per executed row; thread p < d/2 owns pair p of every q and k head, so sin
-// and cos are evaluated once per (row, pair).  With a cache, rotated k and v are also appended at
-// kv_old[seq] + (rank of the row inside its sequence).
-__global__ void __launch_bounds__(64)
+// a layer).  One workgroup per executed row: the d/2 (cos, sin) pairs of the row's position are
+// evaluated once in fp64 into LDS, then every thread rotates 8 pairs of one q or k head with 16-byte
+// accesses.  With a cache, rotated k and v are also appended at kv_old[seq] + (rank of the row inside
+// its sequence).
+__global__ void __launch_bounds__(256)
 rope_append_kernel(RopeArgs a) {
+    __shared__ float cs[64], sn[64];              // head_dim <= 128
     const int i = blockIdx.x;
     if (i >= *a.count) return;
     const int t = a.idx[i];
@@ -136,33 +138,46 @@ rope_append_kernel(RopeArgs a) {
             vdst = reinterpret_cast<half_t*>(a.v_cache) + off;
         }
     }
-    for (int p = threadIdx.x; p < half; p += blockDim.x) {
+    if (threadIdx.x < half) {
+        const int p = threadIdx.x;
         const double inv_freq = pow(static_cast<double>(a.base), -2.0 * static_cast<double>(p) / static_cast<double>(d));
-        double sn, cs;
-        sincos(static_cast<double>(a.positions[t]) * inv_freq, &sn, &cs);
-        const float c = static_cast<float>(cs), s = static_cast<float>(sn);
-        for (int hd = 0; hd < a.nh + a.nkv; ++hd) {
-            half_t* hp = row + static_cast<size_t>(hd) * d;
-            const float lo = static_cast<float>(hp[p]), hi = static_cast<float>(hp[p + half]);
-            const half_t rlo = static_cast<half_t>(lo * c - hi * s);
-            const half_t rhi = static_cast<half_t>(hi * c + lo * s);
-            hp[p] = rlo;
-            hp[p + half] = rhi;
-            if (kdst && hd >= a.nh) {
-                kdst[(hd - a.nh) * d + p] = rlo;
-                kdst[(hd - a.nh) * d + p + half] = rhi;
-            }
+        double s, c;
+        sincos(static_cast<double>(a.positions[t]) * inv_freq, &s, &c);
+        cs[p] = static_cast<float>(c);
+        sn[p] = static_cast<float>(s);
+    }
+    __syncthreads();
+    const int cph = half >> 3;                     // 8-pair chunks per head
+    const int items = (a.nh + a.nkv) * cph;
+    for (int w = threadIdx.x; w < items; w += blockDim.x) {
+        const int hd = w / cph, p0 = (w % cph) * 8;
+        half_t* hp = row + static_cast<size_t>(hd) * d;
+        const half8_t lo = *reinterpret_cast<const half8_t*>(hp + p0);
+        const half8_t hi = *reinterpret_cast<const half8_t*>(hp + p0 + half);
+        half8_t rlo, rhi;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float l = static_cast<float>(lo[e]), h = static_cast<float>(hi[e]);
+            const float c = cs[p0 + e], s = sn[p0 + e];
+            rlo[e] = static_cast<half_t>(l * c - h * s);
+            rhi[e] = static_cast<half_t>(h * c + l * s);
+        }
+        *reinterpret_cast<half8_t*>(hp + p0) = rlo;
+        *reinterpret_cast<half8_t*>(hp + p0 + half) = rhi;
+        if (kdst && hd >= a.nh) {
+            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * d + p0) = rlo;
+            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * d + p0 + half) = rhi;
         }
     }
     if (vdst) {
-        const half_t* vsrc = row + static_cast<size_t>(a.nh + a.nkv) * d;
-        for (int e = threadIdx.x; e < a.nkv * d; e += blockDim.x) vdst[e] = vsrc[e];
+        const half8_t* vsrc = reinterpret_cast<const half8_t*>(row + static_cast<size_t>(a.nh + a.nkv) * d);
+        for (int e = threadIdx.x; e < (a.nkv * d) >> 3; e += blockDim.x) reinterpret_cast<half8_t*>(vdst)[e] = vsrc[e];
     }
 }
 
 hipError_t launch_rope_append(const RopeArgs& a, hipStream_t stream) {
     if (a.max_rows == 0) return hipSuccess;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(a.max_rows), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL(rope_append_kernel, dim3(a.max_rows), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
