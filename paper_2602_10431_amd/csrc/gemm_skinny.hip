@@ -9,8 +9,8 @@
 //     interleaving k-tiles (wave w takes tiles w, w+NW, ...), each wave keeping its own accumulators for
 //     all NFB fragments, so its A registers are reused NFB times;
 //   * per tile a wave issues NFB 16-byte weight loads (1 KB each, contiguous in the prepacked layout),
-//     the scale/zero words and the A fragments straight from global memory in MFMA operand order, two
-//     tiles ahead of use, so ~(2 tiles x (NFB + 8) x 1 KB) are in flight per wave;
+//     the scale/zero words and the A fragments straight from global memory in MFMA operand order; the
+//     weights are prefetched four tiles ahead and the activations two, so ~24 KB are in flight per wave;
 //   * the K-split partial sums meet once, at the end: every wave writes its accumulators as a [64][cols]
 //     fp32 slab into LDS, one barrier, and all threads add the NW slabs in wave order (deterministic)
 //     while applying the same fused epilogues as the prefill kernel with row-contiguous accesses.
@@ -63,21 +63,27 @@ gemm_skinny_kernel(GemmDev p) {
     for (int mf = 0; mf < MF; ++mf)
         a_off[mf] = static_cast<uint32_t>(min(mf * 32 + l32, M - 1)) * static_cast<uint32_t>(p.K) + lhi * 8;
 
-    struct Tile {
-        u32x4_t q[NFB];
-        uint32_t sz[NFB][GPT];
-        half8_t a[MF][4];
-    };
-    auto fetch = [&](int kt, Tile& t) {
+    // Wave w owns tiles w, w + NW, ...  Weights come from HBM (long latency, 5 registers per fragment and
+    // tile) and are prefetched BD tiles ahead; activations come from L2 (16 registers per 32 rows and tile)
+    // and are prefetched two tiles ahead.  Loads past the wave's last tile are clamped to it (harmless,
+    // never consumed) so that the load order in the loop is unconditional.
+    constexpr int BD = NW <= 8 ? 4 : 2;           // weight tiles in flight per wave
+    constexpr int AD = NW <= 8 ? 2 : 1;           // activation tiles in flight per wave
+    u32x4_t bq[BD][NFB];
+    uint32_t bsz[BD][NFB][GPT];
+    half8_t areg[AD][MF][4];
+    auto fetch_b = [&](int kt, u32x4_t* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < NFB; ++fn) {
-            t.q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
+            q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
 #pragma unroll
             for (int g = 0; g < GPT; ++g) {
                 const int gi = (kt * 64 + g * 32) >> p.gshift;
-                t.sz[fn][g] = (sbase[fn] + static_cast<size_t>(gi) * npad[fn])[l32];
+                sz[fn][g] = (sbase[fn] + static_cast<size_t>(gi) * npad[fn])[l32];
             }
         }
+    };
+    auto fetch_a = [&](int kt, half8_t (*ar)[4]) {
         const half_t* base = p.A + kt * 64;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -88,47 +94,42 @@ gemm_skinny_kernel(GemmDev p) {
             }
 #pragma unroll
             for (int mf = 0; mf < MF; ++mf)
-                t.a[mf][j] = *reinterpret_cast<const half8_t*>(base + (a_off[mf] + j * 16 - shift));
+                ar[mf][j] = *reinterpret_cast<const half8_t*>(base + (a_off[mf] + j * 16 - shift));
         }
     };
-    auto compute = [&](const Tile& t) {
+    auto compute = [&](const u32x4_t* q, const uint32_t (*szr)[GPT], const half8_t (*ar)[4]) {
 #pragma unroll
         for (int fn = 0; fn < NFB; ++fn) {
             ScaleZero sz[GPT];
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[g] = expand_sz(t.sz[fn][g]);
+            for (int g = 0; g < GPT; ++g) sz[g] = expand_sz(szr[fn][g]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t wj = j == 0 ? t.q[fn].x : j == 1 ? t.q[fn].y : j == 2 ? t.q[fn].z : t.q[fn].w;
+                const uint32_t wj = j == 0 ? q[fn].x : j == 1 ? q[fn].y : j == 2 ? q[fn].z : q[fn].w;
                 const ScaleZero& s = sz[GPT == 2 ? (j >> 1) : 0];
                 const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
 #pragma unroll
                 for (int mf = 0; mf < MF; ++mf)
-                    acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(t.a[mf][j], b, acc[mf][fn], 0, 0, 0);
+                    acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[mf][j], b, acc[mf][fn], 0, 0, 0);
             }
         }
     };
 
-    // wave w owns tiles w, w + NW, ...  With 8 waves (256 registers each) two tiles are kept in flight;
-    // with 16 waves (128 registers each) one tile, and the four waves per SIMD overlap each other.
-    if (NW <= 8) {
-        Tile t0, t1;
-        int kt = wave;
-        if (kt < p.KT) fetch(kt, t0);
-        if (kt + NW < p.KT) fetch(kt + NW, t1);
-        for (; kt < p.KT; kt += 2 * NW) {
-            compute(t0);
-            if (kt + 2 * NW < p.KT) fetch(kt + 2 * NW, t0);
-            if (kt + NW < p.KT) {
-                compute(t1);
-                if (kt + 3 * NW < p.KT) fetch(kt + 3 * NW, t1);
+    const int n_mine = wave < p.KT ? (p.KT - wave + NW - 1) / NW : 0;     // tiles of this wave
+    if (n_mine > 0) {
+        const int last = wave + (n_mine - 1) * NW;
+#pragma unroll
+        for (int u = 0; u < BD; ++u) fetch_b(min(wave + u * NW, last), bq[u], bsz[u]);
+#pragma unroll
+        for (int u = 0; u < AD; ++u) fetch_a(min(wave + u * NW, last), areg[u]);
+        for (int i0 = 0; i0 < n_mine; i0 += BD) {
+#pragma unroll
+            for (int u = 0; u < BD; ++u) {
+                const int i = i0 + u;
+                if (i < n_mine) compute(bq[u], bsz[u], areg[u % AD]);
+                fetch_a(min(wave + (i + AD) * NW, last), areg[u % AD]);
+                fetch_b(min(wave + (i + BD) * NW, last), bq[u], bsz[u]);
             }
-        }
-    } else {
-        Tile t0;
-        for (int kt = wave; kt < p.KT; kt += NW) {
-            fetch(kt, t0);
-            compute(t0);
         }
     }
 

@@ -1,0 +1,119 @@
+"""Full-size parity (run with -m gpu): one layer at the LLaMA-shaped workloads, in the launch
+configuration bench.py times, checked on what the oracle can afford:
+
+* router scores and the executed set over ALL tokens of the call: bit-exact;
+* hidden states of ONE sequence (attention only couples tokens of the same sequence): the oracle runs
+  the layer on that sequence with the executed set forced to the GPU's/oracle's selection, and every
+  executed row is compared within 2e-2; bypassed rows must be bit-identical to the input;
+* packed codes of one full-size matrix: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import qtale_oracle as orc
+from tests.helpers import cfg_dict, oracle_layer, to_f64
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def qt():
+    import paper_2602_10431_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed):
+    T = B * S
+    tensors = si.layer_tensors(shape, 0, seed, unit_gains=True)
+    x = si.hidden_states(shape, T, seed)
+    offs, pos = si.equal_sequences(B, S)
+    cfg = qt.cfg_from_shape(shape)
+    lw = qt.quantize_layer(tensors, shape.bits, shape.group)
+    ctx = qt.Context()
+    qt.qtale_set_exec_ratio(ctx, ratio)
+    xg = x.cuda()
+    idx = torch.full((T,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    z = torch.empty(T, dtype=torch.float32, device="cuda")
+    qt.qtale_layer_forward(ctx, cfg, lw, xg, offs.cuda(), pos.cuda(), sel_idx=idx, sel_count=cnt, scores=z)
+    torch.cuda.synchronize()
+    # selection over the whole call
+    z_ref = orc.router_scores(to_f64(x), tensors["router_w"].numpy(), 0.0)
+    assert np.array_equal(z.cpu().numpy().view(np.uint32), z_ref.view(np.uint32))
+    want_idx = orc.select_ratio(z_ref, ratio)
+    k = int(cnt.item())
+    assert k == len(want_idx) == orc.executed_count(ratio, T)
+    got_idx = idx[:k].cpu().numpy()
+    assert np.array_equal(got_idx, want_idx)
+    # bypassed rows untouched everywhere
+    got = xg.cpu()
+    skipped = np.setdiff1d(np.arange(T), want_idx)
+    assert torch.equal(got[skipped], x[skipped])
+    # one sequence through the oracle
+    p, q = oracle_layer(shape, 0, seed, tensors=tensors)
+    lo, hi = seq_to_check * S, (seq_to_check + 1) * S
+    local = want_idx[(want_idx >= lo) & (want_idx < hi)] - lo
+    assert len(local) > 0
+    o1, p1 = si.equal_sequences(1, S)
+    want, _, _ = orc.layer_forward(to_f64(x[lo:hi]), p, cfg_dict(shape), o1.numpy(), p1.numpy(), "forced", local)
+    err = orc.parity_error(to_f64(got[lo:hi])[local], want[local])
+    assert err <= TOL, err
+    # codes of the largest matrix
+    codes = q["down"][0]
+    assert np.array_equal(lw.lin["down"].codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes))
+    return err
+
+
+def test_llama7b_shaped_prefill_layer_8x1024_bf16_ratio_half(qt):
+    _prefill_case(qt, si.C2, 8, 1024, 0.5, seq_to_check=3, seed=11)
+
+
+def test_llama3_8b_shaped_gqa_prefill_layer_4x4096_ratio_06(qt):
+    _prefill_case(qt, si.C4, 4, 4096, 0.6, seq_to_check=1, seed=12)
+
+
+def test_llama7b_shaped_decode_step_batch64_ctx2048(qt):
+    shape = si.LayerShape(4096, 32, 32, 128, 11008, 4, 128, "fp16")
+    B, ctx_len, cap, seed = 64, 2048, 2048 + 8, 13
+    tensors = si.layer_tensors(shape, 0, seed, unit_gains=True)
+    x = si.hidden_states(shape, B, seed)
+    offs, pos = si.ragged_sequences([1] * B, starts=[ctx_len] * B)
+    kc, vc = si.kv_cache(shape, B, cap, 0, seed)
+    cfg = qt.cfg_from_shape(shape)
+    lw = qt.quantize_layer(tensors, shape.bits, shape.group)
+    p, _ = oracle_layer(shape, 0, seed, tensors=tensors)
+    z_ref = orc.router_scores(to_f64(x), tensors["router_w"].numpy(), 0.0)
+    ctx = qt.Context()
+    check = [0, 17, 40, 63]
+    for ratio, k_want in [(1.0, 64), (0.8, 51), (0.6, 38), (0.4, 26)]:
+        qt.qtale_set_exec_ratio(ctx, ratio)                      # runtime change, weights untouched
+        kv = qt.KVCache(kc.cuda(), vc.cuda(), torch.full((B,), ctx_len, dtype=torch.int32).cuda())
+        xg = x.cuda()
+        idx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        qt.qtale_layer_forward(ctx, cfg, lw, xg, offs.cuda(), pos.cuda(), kv=kv, sel_idx=idx, sel_count=cnt)
+        torch.cuda.synchronize()
+        want_idx = orc.select_ratio(z_ref, ratio)
+        k = int(cnt.item())
+        assert k == k_want == len(want_idx)
+        assert np.array_equal(idx[:k].cpu().numpy(), want_idx)
+        got = xg.cpu()
+        skipped = np.setdiff1d(np.arange(B), want_idx)
+        assert torch.equal(got[skipped], x[skipped])
+        lens = kv.kv_len.cpu().numpy()
+        executed = np.isin(np.arange(B), want_idx)
+        assert np.array_equal(lens, ctx_len + executed.astype(np.int32))   # bypassed tokens append nothing
+        # a few sequences through the oracle (each decode token only sees its own sequence's cache)
+        sub = [b for b in check if executed[b]] or [int(want_idx[0])]
+        okv = orc.KVCache(to_f64(kc[sub]), to_f64(vc[sub]), [ctx_len] * len(sub))
+        o_s, p_s = si.ragged_sequences([1] * len(sub), starts=[ctx_len] * len(sub))
+        want, _, _ = orc.layer_forward(to_f64(x[sub]), p, cfg_dict(shape), o_s.numpy(), p_s.numpy(), "forced",
+                                       list(range(len(sub))), okv)
+        assert orc.parity_error(to_f64(got[sub]), want) <= TOL
+        gk = to_f64(kv.k.cpu()[sub, ctx_len])
+        gv = to_f64(kv.v.cpu()[sub, ctx_len])
+        assert orc.parity_error(gk, okv.k[:, ctx_len]) <= TOL
+        assert orc.parity_error(gv, okv.v[:, ctx_len]) <= TOL
