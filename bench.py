@@ -51,6 +51,83 @@ def cpu_baseline(shape, seq_len, ratio, n_layers):
                       "stack rate extrapolated as tokens / (%d layers x layer time)" % (seq_len, ratio, dt, n_layers)}
 
 
+def recorded_traffic():
+    """HBM-side bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary, or None
+    when the kernel sources have changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "gate_up_gemm_7b_prefill_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if not line.startswith("#") and ":" in line:
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    h = hashlib.sha256()
+    for rel in ("gemm_w4a16.hip", "gemm_common.h", "qtale_dev.h"):
+        h.update(open(os.path.join(ROOT, "paper_2602_10431_amd", "csrc", rel), "rb").read())
+    if vals.get("kernel_sources_sha256") != h.hexdigest():
+        return None
+    return float(vals["traffic_bytes_per_launch"])
+
+
+def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16):
+    """Secondary measurement (configs[2]): decode steps of the same stack, batch 64, 2048 cached
+    entries per sequence and layer (random fp16 K/V), execution ratio changed at run time."""
+    dev = "cuda"
+    shape = si.LayerShape(4096, 32, 32, 128, 11008, 4, 128, "fp16")
+    cfg = qt.cfg_from_shape(shape)
+    fp16_layers = []
+    for lw in layers:                                  # same quantized weights, fp16 gains for an fp16 stream
+        fp16_layers.append(qt.LayerWeights(lw.lin["q"], lw.lin["k"], lw.lin["v"], lw.lin["o"], lw.lin["gate"],
+                                           lw.lin["up"], lw.lin["down"], lw.norm1.to(torch.float16),
+                                           lw.norm2.to(torch.float16), lw.router_w, lw.router_b))
+    cap = ctx_len + steps + 8
+    kvs = []
+    for l in range(L):
+        k = torch.randn(B, cap, 4096, device=dev, dtype=torch.float16)
+        v = torch.randn(B, cap, 4096, device=dev, dtype=torch.float16)
+        kvs.append(qt.KVCache(k, v, torch.full((B,), ctx_len, dtype=torch.int32, device=dev)))
+    stack = qt.Stack(cfg, fp16_layers, kvs)
+    offs = torch.arange(0, B + 1, dtype=torch.int32, device=dev)
+    ws = qt.alloc_workspace(cfg, B, B, dev)
+    ctx = qt.Context()
+    xs = [si.hidden_states(shape, B, 0, slot="x_step", extra=i, device=dev) for i in range(steps)]
+    res = {}
+    for r in (1.0, 0.8, 0.6, 0.4):
+        qt.qtale_set_exec_ratio(ctx, r)                 # runtime change: no requantization
+        k_exec = int(float(torch.tensor(r, dtype=torch.float32)) * B + 0.5)
+
+        def run(profile):
+            for kv in kvs:
+                kv.kv_len.fill_(ctx_len)
+            torch.cuda.synchronize()
+            qt.qtale_profile_enable(ctx, profile)
+            t0 = time.perf_counter()
+            for i in range(steps):
+                pos = torch.full((B,), ctx_len + i, dtype=torch.int32, device=dev)
+                qt.qtale_stack_forward(ctx, stack, xs[i].clone(), offs, pos, workspace=ws)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+
+        run(False)
+        dt = run(False)
+        run(True)
+        prof = qt.qtale_profile_read(ctx)
+        qt.qtale_profile_enable(ctx, False)
+        ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
+        lin_ms = ms["qkv_gemm"] + ms["o_gemm"] + ms["gate_up_gemm"] + ms["down_gemm"]
+        kv_bytes = k_exec * (ctx_len + steps / 2.0) * 2 * 4096 * 2
+        w_bytes = shape.params_per_layer() // 2 + 4 * (shape.params_per_layer() // 128)
+        res["%.1f" % r] = {"tokens_per_s": B * steps / dt, "ms_per_step": dt * 1e3 / steps,
+                           "executed_per_layer": k_exec,
+                           "attention_ms": ms["attention"], "attention_GBps": kv_bytes / (ms["attention"] * 1e6),
+                           "linears_ms": lin_ms, "weight_stream_GBps": w_bytes / (lin_ms * 1e6)}
+    return {"workload": "configs[2]: same stack in decode, batch %d, %d cached K/V entries per sequence and layer "
+                        "(random fp16), %d steps per ratio, fp16 stream" % (B, ctx_len, steps),
+            "hbm_peak_GBps": HBM_PEAK_GBS, "by_exec_ratio": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +139,9 @@ def main():
     ap.add_argument("--ratio", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (calibrates FETCH_SIZE/WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this build uses no second GPU (run with --gpus 1)")
@@ -103,6 +183,14 @@ def main():
         for x in xs:
             qt.qtale_stack_forward(ctx, stack, x, offs, pos, workspace=ws)
 
+    if args.traffic_probe:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)       # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     run(batches(args.warmup, 1000))
     xs = batches(args.steps, 0)
     torch.cuda.synchronize()
@@ -129,7 +217,7 @@ def main():
     gemm_flops = 2.0 * k_exec * shape.params_per_layer()
     roofline = {"bound": "mfma", "kernel": "qtale::gemm_w4a16_kernel<1,4,4,2,1,2,2,false> (gate/up GEMM with SiLU*up epilogue)",
                 "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": recorded_traffic(),
                 "avg_launch_ms": gu_ms, "flops_per_launch": gu_flops,
                 "all_four_gemms_tflops": gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0}
 
@@ -147,6 +235,11 @@ def main():
             sweep["%.1f" % r] = T * 2 / (time.perf_counter() - t0)
         qt.qtale_set_exec_ratio(ctx, args.ratio)
 
+    decode = None
+    if not args.no_decode:
+        del xs, ws
+        decode = decode_section(qt, si, torch, layers, L)
+
     out = {
         "metric": "tokens/s of quantized token-adaptive layer stack vs exec ratio; % HBM/MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -159,9 +252,9 @@ def main():
         "roofline": roofline,
         "kernel_ms_per_launch": kern_ms,
         "tokens_per_s_vs_exec_ratio": sweep,
+        "decode": decode,
     }
     if not args.no_cpu_baseline:
-        del xs
         out["cpu_baseline"] = cpu_baseline(shape, S, args.ratio, L)
     print(json.dumps(out))
 
