@@ -39,15 +39,17 @@ struct AttnDev {
 };
 
 template <int D>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 flash_prefill_kernel(AttnDev p) {
     constexpr int KS = D / 16;          // k-steps of the QK^T product
     constexpr int DF = D / 32;          // 32-wide fragments of the head dimension
     constexpr int KSTR = D + 8;         // LDS row stride of the K tile (halves)
     constexpr int VSTR = 64 + 4;        // LDS row stride of the transposed V tile (halves)
-    constexpr int CH = (64 * D / 8) / 256;   // 16-byte chunks per thread per tile
-    __shared__ __attribute__((aligned(16))) half_t Ks[64 * KSTR];
-    __shared__ __attribute__((aligned(16))) half_t Vt[D * VSTR];
+    constexpr int CPR = D / 8;          // 16-byte chunks per K/V row
+    constexpr int CH = (64 * CPR) / 256;     // K chunks per thread per tile
+    constexpr int VG = (16 * CPR + 255) / 256;   // V groups (4 keys x 8 columns) per thread per tile
+    __shared__ __attribute__((aligned(16))) half_t Ks2[2][64 * KSTR];    // double-buffered tiles
+    __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VSTR];
 
     const int item = blockIdx.x;
     if (item >= *p.n_items) return;
@@ -74,8 +76,8 @@ flash_prefill_kernel(AttnDev p) {
         kbase = p.qkv + static_cast<size_t>(row_begin) * p.width + (p.nh + hk) * D;
         vbase = kbase + p.nkv * D;
     }
-    const int q_lo = qt * 128;                                   // first local query index of the block
-    const int q_cnt = min(128, n_b - q_lo);
+    const int q_lo = qt * kAttnBQ;                               // first local query index of the block
+    const int q_cnt = min(kAttnBQ, n_b - q_lo);
     int n_keys = base_len + q_lo + q_cnt;                        // keys visible to the last query
     if (p.k_cache) n_keys = min(n_keys, p.cap);
     const int n_tiles = (n_keys + 63) / 64;
@@ -83,11 +85,17 @@ flash_prefill_kernel(AttnDev p) {
     // this lane's query (column of S^T): local index inside the sequence, clamped to a valid row
     const int q_local = q_lo + min(wave * 32 + l32, q_cnt - 1);
     const int limit = base_len + q_local + 1;                    // keys [0, limit) are visible
-    const int wave_limit = base_len + q_lo + min(wave * 32 + 31, q_cnt - 1) + 1;
+    const int wave_hi = base_len + q_lo + min(wave * 32 + 31, q_cnt - 1) + 1;   // largest limit in the wave
+    const int wave_lo = base_len + q_lo + min(wave * 32, q_cnt - 1) + 1;        // smallest limit in the wave
     const half_t* qrow = p.qkv + static_cast<size_t>(row_begin + q_local) * p.width + h * D;
     half8_t qf[KS];
+    const half_t qs = static_cast<half_t>(p.scale_log2);         // fold log2(e)/sqrt(d) into the queries
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * lhi);
+    for (int s = 0; s < KS; ++s) {
+        qf[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * lhi);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[s][e] *= qs;
+    }
 
     float16_t o[DF];
 #pragma unroll
@@ -96,50 +104,69 @@ flash_prefill_kernel(AttnDev p) {
         for (int r = 0; r < 16; ++r) o[df][r] = 0.0f;
     float m_run = kNegBig, l_run = 0.0f;
 
-    // global -> register staging of one K/V tile: chunk c is key c / (D/8), 8 halves at (c % (D/8))*8.
-    // V is transposed on its way into LDS (Vt[column][key]).
-    U4 kreg[CH], vreg[CH];
+    // global -> register staging of one tile.  K: chunk c is key c / CPR, 8 halves at (c % CPR)*8.
+    // V: a thread owns 4 consecutive keys x 8 columns and transposes them in registers, so that the
+    // transposed tile Vt[column][key] is written with 8-byte stores.
+    u32x4_t kreg[CH], vreg[VG][4];
     auto fetch = [&](int tile) {
         const int key0 = tile * 64;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = i * 256 + tid;
-            const int key = min(key0 + c / (D / 8), n_keys - 1);
-            kreg[i] = *reinterpret_cast<const U4*>(kbase + static_cast<size_t>(key) * kv_stride + (c % (D / 8)) * 8);
+            const int key = min(key0 + c / CPR, n_keys - 1);
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + static_cast<size_t>(key) * kv_stride + (c % CPR) * 8);
         }
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = i * 256 + tid;
-            const int key = min(key0 + c / (D / 8), n_keys - 1);
-            vreg[i] = *reinterpret_cast<const U4*>(vbase + static_cast<size_t>(key) * kv_stride + (c % (D / 8)) * 8);
+        for (int i = 0; i < VG; ++i) {
+            const int g = min(i * 256 + tid, 16 * CPR - 1);
+            const int kg = g / CPR, dc = g % CPR;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int key = min(key0 + 4 * kg + u, n_keys - 1);
+                vreg[i][u] = *reinterpret_cast<const u32x4_t*>(vbase + static_cast<size_t>(key) * kv_stride + dc * 8);
+            }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf) {
+        half_t* Ks = Ks2[buf];
+        half_t* Vt = Vt2[buf];
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = i * 256 + tid;
-            *reinterpret_cast<U4*>(&Ks[(c / (D / 8)) * KSTR + (c % (D / 8)) * 8]) = kreg[i];
+            *reinterpret_cast<u32x4_t*>(&Ks[(c / CPR) * KSTR + (c % CPR) * 8]) = kreg[i];
         }
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = i * 256 + tid;
-            const int key = c / (D / 8), d0 = (c % (D / 8)) * 8;
-            const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
+        for (int i = 0; i < VG; ++i) {
+            const int g = i * 256 + tid;
+            if (g >= 16 * CPR) continue;
+            const int kg = g / CPR, dc = g % CPR;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                reinterpret_cast<uint16_t*>(Vt)[(d0 + 2 * e) * VSTR + key] = static_cast<uint16_t>(w[e] & 0xffffu);
-                reinterpret_cast<uint16_t*>(Vt)[(d0 + 2 * e + 1) * VSTR + key] = static_cast<uint16_t>(w[e] >> 16);
+            for (int w = 0; w < 4; ++w) {                        // word w holds columns 2w, 2w+1 of each key
+                const uint32_t a0 = vreg[i][0][w], a1 = vreg[i][1][w], a2 = vreg[i][2][w], a3 = vreg[i][3][w];
+                uint2 even, odd;
+                even.x = (a0 & 0xffffu) | (a1 << 16);
+                even.y = (a2 & 0xffffu) | (a3 << 16);
+                odd.x = (a0 >> 16) | (a1 & 0xffff0000u);
+                odd.y = (a2 >> 16) | (a3 & 0xffff0000u);
+                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w) * VSTR + 4 * kg]) = even;
+                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w + 1) * VSTR + 4 * kg]) = odd;
             }
         }
     };
 
+    // Tile t+1 is parked in the other LDS buffer and tile t+2 requested before tile t is computed: one
+    // barrier per tile, and the staging of one wave overlaps the MFMAs of the others.
     fetch(0);
+    stage(0);
+    if (n_tiles > 1) fetch(1);
+    __syncthreads();
     for (int tile = 0; tile < n_tiles; ++tile) {
-        stage();
-        __syncthreads();
-        if (tile + 1 < n_tiles) fetch(tile + 1);
+        if (tile + 1 < n_tiles) stage((tile + 1) & 1);
+        if (tile + 2 < n_tiles) fetch(tile + 2);
+        const half_t* Ks = Ks2[tile & 1];
+        const half_t* Vt = Vt2[tile & 1];
         const int key0 = tile * 64;
-        if (key0 < wave_limit) {
+        if (key0 < wave_hi) {
             // S^T = K Q^T : rows = keys (two 32-key fragments), column = this lane's query
             float16_t st[2];
 #pragma unroll
@@ -152,36 +179,44 @@ flash_prefill_kernel(AttnDev p) {
                     st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qf[s], st[kf], 0, 0, 0);
                 }
             }
-            // online softmax over the 32 scores this lane holds (the lane 32 away holds the other 32)
+            // online softmax over the 32 scores this lane holds (the lane 32 away holds the other 32);
+            // only tiles that reach past the wave's smallest causal limit need the mask
+            if (key0 + 64 > wave_lo) {
+#pragma unroll
+                for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + kf * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+                        if (key >= limit) st[kf][r] = kNegBig;
+                    }
+            }
             float mx = kNegBig;
 #pragma unroll
             for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + kf * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-                    const float s = key < limit ? st[kf][r] * p.scale_log2 : kNegBig;
-                    st[kf][r] = s;
-                    mx = fmaxf(mx, s);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kf][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m_run, mx);
-            const float alpha = exp2f(m_run - m_new);
-            m_run = m_new;
             float psum = 0.0f;
             half8_t pf[4];
 #pragma unroll
             for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pv = exp2f(st[kf][r] - m_new);
+                    const float pv = __builtin_amdgcn_exp2f(st[kf][r] - m_new);
                     psum += pv;
                     pf[kf * 2 + (r >> 3)][r & 7] = static_cast<half_t>(pv);
                 }
-            l_run = l_run * alpha + psum;
+            if (__any(m_new != m_run)) {                         // rescale only when some maximum moved
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= alpha;
 #pragma unroll
-            for (int df = 0; df < DF; ++df)
+                for (int df = 0; df < DF; ++df)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[df][r] *= alpha;
+                    for (int r = 0; r < 16; ++r) o[df][r] *= alpha;
+                m_run = m_new;
+            }
+            l_run += psum;
             // O^T += V^T P^T : k-step s2 covers keys 16 s2 .. 16 s2 + 15 of the tile; operand element e of a
             // lane is key 16 s2 + 8 (e/4) + 4 (lane/32) + e%4, the order the accumulator layout produced
 #pragma unroll
