@@ -9,8 +9,8 @@
 //     interleaving k-tiles (wave w takes tiles w, w+NW, ...), each wave keeping its own accumulators for
 //     all NFB fragments, so its A registers are reused NFB times;
 //   * per tile a wave issues NFB 16-byte weight loads (1 KB each, contiguous in the prepacked layout),
-//     the scale/zero words and the A fragments straight from global memory in MFMA operand order; the
-//     weights are prefetched four tiles ahead and the activations two, so ~24 KB are in flight per wave;
+//     the scale/zero words and its A tile (row-contiguous loads, re-laid out through a wave-private LDS
+//     region); the weights are prefetched four tiles ahead and the activations two;
 //   * the K-split partial sums meet once, at the end: every wave writes its accumulators as a [64][cols]
 //     fp32 slab into LDS, one barrier, and all threads add the NW slabs in wave order (deterministic)
 //     while applying the same fused epilogues as the prefill kernel with row-contiguous accesses.
@@ -20,13 +20,18 @@
 namespace qtale {
 
 template <int NFB, int NW, int MF, int GPT, int EPI, bool RAGGED>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64, (NW <= 4 ? 2 : 1))
 gemm_skinny_kernel(GemmDev p) {
     constexpr int NT = NW * 64;
     constexpr int CW = NFB * 32;                 // accumulator columns per wave
     constexpr int CSTR = CW + 4;                 // slab row stride (floats)
     constexpr int ROWS = MF * 32;
-    __shared__ __attribute__((aligned(16))) float slab[NW * ROWS * CSTR];
+    constexpr int AD = (NW <= 8 && MF == 1) ? 2 : 1;   // activation tiles staged in LDS per wave (ring)
+    constexpr int ASTR = 72;                     // halves per staged A row (64 + 8: conflict-free 16-byte reads)
+    constexpr int kSlabBytes = NW * ROWS * CSTR * 4;
+    constexpr int kStageBytes = NW * AD * ROWS * ASTR * 2;
+    __shared__ __attribute__((aligned(16))) char smem[kSlabBytes > kStageBytes ? kSlabBytes : kStageBytes];
+    float* slab = reinterpret_cast<float*>(smem);
 
     const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
     if (M <= 0) return;
@@ -57,21 +62,28 @@ gemm_skinny_kernel(GemmDev p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mf][fn][r] = 0.0f;
 
-    // per-lane A row offsets (rows clamped to M-1: their results are never stored)
-    uint32_t a_off[MF];
+    // Activations: a wave fetches its k-tile of A (ROWS x 64 halves) with row-contiguous 16-byte loads (8
+    // lanes per 128-byte row segment, so every cache line is consumed by the instruction that fetched it),
+    // parks it in a wave-private LDS region and reads it back in MFMA operand order.  Reading the operand
+    // layout straight from global memory touches each line with four different instructions and, with
+    // 16 tiles in flight per CU, thrashes the 32 KB L1: that version moved four times the bytes.
+    constexpr int A_LD = ROWS / 8;                   // 16-byte loads per lane per tile
+    uint32_t a_off[A_LD];
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf)
-        a_off[mf] = static_cast<uint32_t>(min(mf * 32 + l32, M - 1)) * static_cast<uint32_t>(p.K) + lhi * 8;
+    for (int it = 0; it < A_LD; ++it)
+        a_off[it] = static_cast<uint32_t>(min(it * 8 + (lane >> 3), M - 1)) * static_cast<uint32_t>(p.K) + (lane & 7) * 8;
+    half_t* stage_base = reinterpret_cast<half_t*>(smem) + wave * (AD * ROWS * ASTR);
+    const int st_w = (lane >> 3) * ASTR + (lane & 7) * 8;          // where this lane parks its chunk (+ it*8 rows)
+    const int st_r = l32 * ASTR + lhi * 8;                          // where it reads operand (mf, j) from
 
     // Wave w owns tiles w, w + NW, ...  Weights come from HBM (long latency, 5 registers per fragment and
-    // tile) and are prefetched BD tiles ahead; activations come from L2 (16 registers per 32 rows and tile)
-    // and are prefetched two tiles ahead.  Loads past the wave's last tile are clamped to it (harmless,
-    // never consumed) so that the load order in the loop is unconditional.
+    // tile) and are prefetched BD tiles ahead; activations come from L2 and are prefetched AD tiles ahead
+    // in registers.  Loads past the wave's last tile are clamped to it (harmless, never consumed) so that
+    // the load order in the loop is unconditional.
     constexpr int BD = NW <= 8 ? 4 : 2;           // weight tiles in flight per wave
-    constexpr int AD = NW <= 8 ? 2 : 1;           // activation tiles in flight per wave
     u32x4_t bq[BD][NFB];
     uint32_t bsz[BD][NFB][GPT];
-    half8_t areg[AD][MF][4];
+    u32x4_t areg[AD][A_LD];
     auto fetch_b = [&](int kt, u32x4_t* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < NFB; ++fn) {
@@ -83,34 +95,41 @@ gemm_skinny_kernel(GemmDev p) {
             }
         }
     };
-    auto fetch_a = [&](int kt, half8_t (*ar)[4]) {
+    auto fetch_a = [&](int kt, u32x4_t* ar) {
         const half_t* base = p.A + kt * 64;
+        uint32_t shift = 0;
+        if (RAGGED) {                               // chunks starting at or beyond K read the row's last
+            const int col = kt * 64 + (lane & 7) * 8;           // valid chunk: the weights there are 0
+            shift = col >= p.K ? static_cast<uint32_t>(col - (p.K - 8)) : 0u;
+        }
+#pragma unroll
+        for (int it = 0; it < A_LD; ++it) ar[it] = *reinterpret_cast<const u32x4_t*>(base + (a_off[it] - shift));
+    };
+    auto park_a = [&](const u32x4_t* ar, int slot) {
+        half_t* dst = stage_base + slot * (ROWS * ASTR) + st_w;
+#pragma unroll
+        for (int it = 0; it < A_LD; ++it) *reinterpret_cast<u32x4_t*>(dst + it * 8 * ASTR) = ar[it];
+    };
+    auto compute = [&](const u32x4_t* q, const uint32_t (*szr)[GPT], int slot) {
+        const half_t* src = stage_base + slot * (ROWS * ASTR) + st_r;
+        ScaleZero sz[NFB][GPT];
+#pragma unroll
+        for (int fn = 0; fn < NFB; ++fn)
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(szr[fn][g]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t shift = 0;
-            if (RAGGED) {                           // chunks starting at or beyond K read the row's last
-                const int col = kt * 64 + j * 16 + lhi * 8;     // valid chunk: the weights there are 0
-                shift = col >= p.K ? static_cast<uint32_t>(col - (p.K - 8)) : 0u;
-            }
+            half8_t a[MF];
 #pragma unroll
-            for (int mf = 0; mf < MF; ++mf)
-                ar[mf][j] = *reinterpret_cast<const half8_t*>(base + (a_off[mf] + j * 16 - shift));
-        }
-    };
-    auto compute = [&](const u32x4_t* q, const uint32_t (*szr)[GPT], const half8_t (*ar)[4]) {
+            for (int mf = 0; mf < MF; ++mf) a[mf] = *reinterpret_cast<const half8_t*>(src + mf * 32 * ASTR + j * 16);
 #pragma unroll
-        for (int fn = 0; fn < NFB; ++fn) {
-            ScaleZero sz[GPT];
-#pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[g] = expand_sz(szr[fn][g]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int fn = 0; fn < NFB; ++fn) {
                 const uint32_t wj = j == 0 ? q[fn].x : j == 1 ? q[fn].y : j == 2 ? q[fn].z : q[fn].w;
-                const ScaleZero& s = sz[GPT == 2 ? (j >> 1) : 0];
+                const ScaleZero& s = sz[fn][GPT == 2 ? (j >> 1) : 0];
                 const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
 #pragma unroll
                 for (int mf = 0; mf < MF; ++mf)
-                    acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ar[mf][j], b, acc[mf][fn], 0, 0, 0);
+                    acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mf], b, acc[mf][fn], 0, 0, 0);
             }
         }
     };
@@ -126,12 +145,16 @@ gemm_skinny_kernel(GemmDev p) {
 #pragma unroll
             for (int u = 0; u < BD; ++u) {
                 const int i = i0 + u;
-                if (i < n_mine) compute(bq[u], bsz[u], areg[u % AD]);
+                // the LDS slot of tile i was last read by tile i - AD of this same wave (LDS ops of a wave
+                // complete in order), so parking needs no barrier
+                park_a(areg[u % AD], u % AD);
                 fetch_a(min(wave + (i + AD) * NW, last), areg[u % AD]);
+                if (i < n_mine) compute(bq[u], bsz[u], u % AD);
                 fetch_b(min(wave + (i + BD) * NW, last), bq[u], bsz[u]);
             }
         }
     }
+    __syncthreads();     // the slabs below overlay the A staging regions of other waves
 
     // ---- meet: slabs into LDS, one barrier, ordered sum + epilogue ----------------------------------
     float* mine = slab + wave * (ROWS * CSTR);
@@ -214,15 +237,21 @@ static hipError_t launch_one(GemmDev& d, hipStream_t stream) {
 
 template <int GPT, int EPI>
 static hipError_t launch_shape(GemmDev& d, hipStream_t stream) {
-    // SwiGLU needs gate and up fragments side by side; otherwise narrow linears (few fragments) use one
-    // fragment per workgroup and 16 K-slices so that more CUs take part.
-    const bool wide = EPI == EPI_SWIGLU_F16 || d.vf_total >= 256;
-    if (d.M_max <= 32) {
-        if (wide) return launch_one<2, 8, 1, GPT, EPI>(d, stream);
-        return launch_one<(EPI == EPI_SWIGLU_F16 ? 2 : 1), (EPI == EPI_SWIGLU_F16 ? 8 : 16), 1, GPT, EPI>(d, stream);
+    // Pick the split so that one round of workgroups covers the chip: very wide outputs (gate/up) use four
+    // waves per workgroup and two workgroups per CU, wide ones eight waves, narrow ones (few fragments)
+    // one fragment per workgroup and 16 K-slices so that more CUs take part.
+    if (EPI == EPI_SWIGLU_F16 || d.vf_total >= 512) {
+        if (d.M_max <= 32) return launch_one<2, 4, 1, GPT, EPI>(d, stream);
+        return launch_one<2, 4, 2, GPT, EPI>(d, stream);
     }
-    if (wide) return launch_one<2, 8, 2, GPT, EPI>(d, stream);
-    return launch_one<(EPI == EPI_SWIGLU_F16 ? 2 : 1), (EPI == EPI_SWIGLU_F16 ? 8 : 16), 2, GPT, EPI>(d, stream);
+    if (d.vf_total >= 256) {
+        if (d.M_max <= 32) return launch_one<2, 8, 1, GPT, EPI>(d, stream);
+        return launch_one<2, 8, 2, GPT, EPI>(d, stream);
+    }
+    constexpr int NFBn = EPI == EPI_SWIGLU_F16 ? 2 : 1;
+    constexpr int NWn = EPI == EPI_SWIGLU_F16 ? 8 : 16;
+    if (d.M_max <= 32) return launch_one<NFBn, NWn, 1, GPT, EPI>(d, stream);
+    return launch_one<NFBn, NWn, 2, GPT, EPI>(d, stream);
 }
 
 template <int GPT>
