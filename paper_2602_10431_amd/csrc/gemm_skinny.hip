@@ -38,6 +38,7 @@ gemm_skinny_kernel(GemmDev p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
+    const uint32_t magic = dequant_magic();
     const int tile_n = blockIdx.x;
 
     const u32x4_t* bbase[NFB];
@@ -126,7 +127,7 @@ gemm_skinny_kernel(GemmDev p) {
             for (int fn = 0; fn < NFB; ++fn) {
                 const uint32_t wj = j == 0 ? q[fn].x : j == 1 ? q[fn].y : j == 2 ? q[fn].z : q[fn].w;
                 const ScaleZero& s = sz[fn][GPT == 2 ? (j >> 1) : 0];
-                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi);
+                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi, magic);
 #pragma unroll
                 for (int mf = 0; mf < MF; ++mf)
                     acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mf], b, acc[mf][fn], 0, 0, 0);
@@ -248,10 +249,11 @@ static hipError_t launch_shape(GemmDev& d, hipStream_t stream) {
         if (d.M_max <= 32) return launch_one<2, 8, 1, GPT, EPI>(d, stream);
         return launch_one<2, 8, 2, GPT, EPI>(d, stream);
     }
-    constexpr int NFBn = EPI == EPI_SWIGLU_F16 ? 2 : 1;
-    constexpr int NWn = EPI == EPI_SWIGLU_F16 ? 8 : 16;
-    if (d.M_max <= 32) return launch_one<NFBn, NWn, 1, GPT, EPI>(d, stream);
-    return launch_one<NFBn, NWn, 2, GPT, EPI>(d, stream);
+    if constexpr (EPI != EPI_SWIGLU_F16) {
+        if (d.M_max <= 32) return launch_one<1, 16, 1, GPT, EPI>(d, stream);
+        return launch_one<1, 16, 2, GPT, EPI>(d, stream);
+    }
+    return hipErrorInvalidValue;       // SwiGLU always takes the first branch
 }
 
 template <int GPT>

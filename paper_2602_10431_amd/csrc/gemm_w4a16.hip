@@ -48,6 +48,7 @@ gemm_w4a16_kernel(GemmDev p) {
     const int wn = wave / WM;
     const int l32 = lane & 31;
     const int lhi = lane >> 5;
+    const uint32_t magic = dequant_magic();
 
     // ---- which weight fragments this wave owns (all wave-uniform -> scalar base addresses) ------
     const u32x4_t* bbase[FN];
@@ -169,7 +170,7 @@ gemm_w4a16_kernel(GemmDev p) {
         };
         const half_t* Ab = &As[buf][a_row0];
         const half_t* An = &As[nbuf][a_row0];
-        half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi);
+        half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi, magic);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j == 1) {
@@ -187,7 +188,7 @@ gemm_w4a16_kernel(GemmDev p) {
                 half8_t bnext = bcur;
                 if (jn < 4) {
                     const ScaleZero& sn = sz[fnn][GPT == 2 ? (jn >> 1) : 0];
-                    bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi);
+                    bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi, magic);
                 }
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
