@@ -1,62 +1,82 @@
 // Row-wise kernels on the compacted (executed) tokens: gather + RMSNorm, RMSNorm of the fp32 residual,
 // rotary embedding at the token's original position with optional K/V cache append.
-// All are bandwidth-bound: 16-byte loads, one wave per row, fp32 reductions.
+// All are bandwidth-bound: 16-byte loads, one workgroup per row, fp32 reductions.
 #include "qtale_dev.h"
 #include "qtale_kernels.h"
 
 namespace qtale {
 
-// out[i] = fp16( x[idx[i]] / sqrt(mean(x^2) + eps) * gain ), one wave per executed row (App. B.2 gather
-// fused with the layer's first normalisation).
+// Sum over the 256 threads of a workgroup (4 waves), result in every thread.
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// out[i] = fp16( x[idx[i]] / sqrt(mean(x^2) + eps) * gain ), one workgroup per executed row (App. B.2
+// gather fused with the layer's first normalisation).  A thread keeps its 8-element chunks in registers
+// between the reduction and the scaling (up to 8192 columns; wider rows re-read from L2).
 template <bool BF16>
 __global__ void __launch_bounds__(256)
 gather_rmsnorm_kernel(const uint16_t* __restrict__ x, int H, const int32_t* __restrict__ idx,
                       const int32_t* __restrict__ count, const uint16_t* __restrict__ gain, float eps,
                       uint16_t* __restrict__ out) {
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ float red[4];
+    const int i = blockIdx.x;
     if (i >= *count) return;
     const int t = idx[i];
-    const U4* xr = reinterpret_cast<const U4*>(x + static_cast<size_t>(t) * H);
-    const U4* gr = reinterpret_cast<const U4*>(gain);
-    U4* orow = reinterpret_cast<U4*>(out + static_cast<size_t>(i) * H);
+    const u32x4_t* xr = reinterpret_cast<const u32x4_t*>(x + static_cast<size_t>(t) * H);
+    const u32x4_t* gr = reinterpret_cast<const u32x4_t*>(gain);
+    u32x4_t* orow = reinterpret_cast<u32x4_t*>(out + static_cast<size_t>(i) * H);
     const int chunks = H >> 3;
+    constexpr int KEEP = 4;
+    u32x4_t keep[KEEP];
     float ss = 0.0f;
-    for (int c = lane; c < chunks; c += 64) {
-        const U4 v = xr[c];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        keep[u] = c < chunks ? xr[c] : u32x4_t{0u, 0u, 0u, 0u};
+    }
+    auto sumsq = [&](const u32x4_t& v) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float a = act_to_float<BF16>(static_cast<uint16_t>(w[j] & 0xffffu));
-            const float b = act_to_float<BF16>(static_cast<uint16_t>(w[j] >> 16));
+            const float a = act_to_float<BF16>(static_cast<uint16_t>(v[j] & 0xffffu));
+            const float b = act_to_float<BF16>(static_cast<uint16_t>(v[j] >> 16));
             ss = fmaf(a, a, ss);
             ss = fmaf(b, b, ss);
         }
-    }
-    ss = wave_sum(ss);
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) sumsq(keep[u]);
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) sumsq(xr[c]);
+    ss = block_sum_256(ss, red);
     const float inv = 1.0f / sqrtf(ss / static_cast<float>(H) + eps);
-    for (int c = lane; c < chunks; c += 64) {
-        const U4 v = xr[c];
-        const U4 g = gr[c];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
-        uint32_t o[4];
+    auto emit = [&](int c, const u32x4_t& v) {
+        const u32x4_t g = gr[c];
+        u32x4_t o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float a = act_to_float<BF16>(static_cast<uint16_t>(w[j] & 0xffffu)) * inv *
-                            act_to_float<BF16>(static_cast<uint16_t>(gw[j] & 0xffffu));
-            const float b = act_to_float<BF16>(static_cast<uint16_t>(w[j] >> 16)) * inv *
-                            act_to_float<BF16>(static_cast<uint16_t>(gw[j] >> 16));
+            const float a = act_to_float<BF16>(static_cast<uint16_t>(v[j] & 0xffffu)) * inv *
+                            act_to_float<BF16>(static_cast<uint16_t>(g[j] & 0xffffu));
+            const float b = act_to_float<BF16>(static_cast<uint16_t>(v[j] >> 16)) * inv *
+                            act_to_float<BF16>(static_cast<uint16_t>(g[j] >> 16));
             o[j] = static_cast<uint32_t>(float_to_half_bits(a)) | (static_cast<uint32_t>(float_to_half_bits(b)) << 16);
         }
-        orow[c] = U4{o[0], o[1], o[2], o[3]};
+        orow[c] = o;
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        if (c < chunks) emit(c, keep[u]);
     }
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) emit(c, xr[c]);
 }
 
 hipError_t launch_gather_rmsnorm(const void* x, int bf16, int H, const int32_t* idx, const int32_t* count,
                                  int max_rows, const void* gain, float eps, void* out_f16, hipStream_t stream) {
     if (max_rows == 0) return hipSuccess;
-    const dim3 grid((max_rows + 3) / 4), block(256);
+    const dim3 grid(max_rows), block(256);
     if (bf16)
         hipLaunchKernelGGL(gather_rmsnorm_kernel<true>, grid, block, 0, stream, reinterpret_cast<const uint16_t*>(x),
                            H, idx, count, reinterpret_cast<const uint16_t*>(gain), eps, reinterpret_cast<uint16_t*>(out_f16));
@@ -66,43 +86,61 @@ hipError_t launch_gather_rmsnorm(const void* x, int bf16, int H, const int32_t* 
     return hipGetLastError();
 }
 
-// out[i] = fp16( h[i] / sqrt(mean(h^2) + eps) * gain ) for the fp32 post-attention residual h.
+// out[i] = fp16( h[i] / sqrt(mean(h^2) + eps) * gain ) for the fp32 post-attention residual h; one
+// workgroup per row, the row held in registers between the two steps (up to 8192 columns).
 template <bool BF16>
 __global__ void __launch_bounds__(256)
 rmsnorm_f32_kernel(const float* __restrict__ h, int H, const int32_t* __restrict__ count,
                    const uint16_t* __restrict__ gain, float eps, uint16_t* __restrict__ out) {
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ float red[4];
+    const int i = blockIdx.x;
     if (i >= *count) return;
-    const float4* hr = reinterpret_cast<const float4*>(h + static_cast<size_t>(i) * H);
+    const float4_t* hr = reinterpret_cast<const float4_t*>(h + static_cast<size_t>(i) * H);
     const U2* gr = reinterpret_cast<const U2*>(gain);
     U2* orow = reinterpret_cast<U2*>(out + static_cast<size_t>(i) * H);
     const int chunks = H >> 2;
+    constexpr int KEEP = 8;
+    float4_t keep[KEEP];
     float ss = 0.0f;
-    for (int c = lane; c < chunks; c += 64) {
-        const float4 v = hr[c];
-        ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        keep[u] = c < chunks ? hr[c] : float4_t{0.f, 0.f, 0.f, 0.f};
     }
-    ss = wave_sum(ss);
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss = fmaf(keep[u][e], keep[u][e], ss);
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) {
+        const float4_t v = hr[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss = fmaf(v[e], v[e], ss);
+    }
+    ss = block_sum_256(ss, red);
     const float inv = 1.0f / sqrtf(ss / static_cast<float>(H) + eps);
-    for (int c = lane; c < chunks; c += 64) {
-        const float4 v = hr[c];
+    auto emit = [&](int c, const float4_t& v) {
         const U2 g = gr[c];
         const float g0 = act_to_float<BF16>(static_cast<uint16_t>(g.x & 0xffffu));
         const float g1 = act_to_float<BF16>(static_cast<uint16_t>(g.x >> 16));
         const float g2 = act_to_float<BF16>(static_cast<uint16_t>(g.y & 0xffffu));
         const float g3 = act_to_float<BF16>(static_cast<uint16_t>(g.y >> 16));
         U2 o;
-        o.x = static_cast<uint32_t>(float_to_half_bits(v.x * inv * g0)) | (static_cast<uint32_t>(float_to_half_bits(v.y * inv * g1)) << 16);
-        o.y = static_cast<uint32_t>(float_to_half_bits(v.z * inv * g2)) | (static_cast<uint32_t>(float_to_half_bits(v.w * inv * g3)) << 16);
+        o.x = static_cast<uint32_t>(float_to_half_bits(v[0] * inv * g0)) | (static_cast<uint32_t>(float_to_half_bits(v[1] * inv * g1)) << 16);
+        o.y = static_cast<uint32_t>(float_to_half_bits(v[2] * inv * g2)) | (static_cast<uint32_t>(float_to_half_bits(v[3] * inv * g3)) << 16);
         orow[c] = o;
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        if (c < chunks) emit(c, keep[u]);
     }
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) emit(c, hr[c]);
 }
 
 hipError_t launch_rmsnorm_f32(const float* h, int H, const int32_t* count, int max_rows, const void* gain,
                               int gain_bf16, float eps, void* out_f16, hipStream_t stream) {
     if (max_rows == 0) return hipSuccess;
-    const dim3 grid((max_rows + 3) / 4), block(256);
+    const dim3 grid(max_rows), block(256);
     if (gain_bf16)
         hipLaunchKernelGGL(rmsnorm_f32_kernel<true>, grid, block, 0, stream, h, H, count,
                            reinterpret_cast<const uint16_t*>(gain), eps, reinterpret_cast<uint16_t*>(out_f16));
