@@ -90,25 +90,61 @@ def quantize_rtn(W, bits=4, group=128):
 
 
 def pack_codes(codes, bits=4):
-    """Canonical packing of 4-bit codes: uint32 [N, ceil(K/8)], nibble j of word w holds
-    the code of k = 8*w + j (least-significant nibble first); rows are padded with code 0."""
-    assert bits == 4
+    """Canonical packing of the codes of one matrix, uint32 [N, words per row].
+
+    4 bit: ceil(K/8) words per row, nibble j of word w holds the code of k = 8*w + j
+    (least-significant nibble first); rows are padded with code 0.
+    3 bit: the codes of a row form one little-endian bit stream, code k at bits [3k, 3k+3), cut into
+    32-bit words (32 codes fill exactly 3 words); rows are padded with code 0 to a whole number of
+    32-code blocks, i.e. 3*ceil(K/32) words per row."""
     N, K = codes.shape
-    nw = (K + 7) // 8
-    padded = np.zeros((N, nw * 8), dtype=np.uint32)
+    if bits == 4:
+        nw = (K + 7) // 8
+        padded = np.zeros((N, nw * 8), dtype=np.uint32)
+        padded[:, :K] = codes
+        out = np.zeros((N, nw), dtype=np.uint32)
+        for j in range(8):
+            out |= padded[:, j::8] << np.uint32(4 * j)
+        return out
+    assert bits == 3
+    nb = (K + 31) // 32
+    padded = np.zeros((N, nb * 32), dtype=np.uint64)
     padded[:, :K] = codes
-    out = np.zeros((N, nw), dtype=np.uint32)
-    for j in range(8):
-        out |= padded[:, j::8] << np.uint32(4 * j)
+    out = np.zeros((N, nb * 3), dtype=np.uint32)
+    for b in range(nb):
+        lo = np.zeros(N, dtype=np.uint64)                       # bits 0..62 of the block's 96-bit stream
+        hi = np.zeros(N, dtype=np.uint64)                       # bits 63..95
+        for j in range(32):
+            c = padded[:, b * 32 + j]
+            if j < 21:
+                lo |= c << np.uint64(3 * j)
+            else:
+                hi |= c << np.uint64(3 * j - 63)
+        full_lo = lo | ((hi & np.uint64(1)) << np.uint64(63))   # bits 0..63
+        rest = hi >> np.uint64(1)                               # bits 64..95
+        out[:, 3 * b] = (full_lo & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+        out[:, 3 * b + 1] = (full_lo >> np.uint64(32)).astype(np.uint32)
+        out[:, 3 * b + 2] = (rest & np.uint64(0xFFFFFFFF)).astype(np.uint32)
     return out
 
 
 def unpack_codes(words, K, bits=4):
-    assert bits == 4
     N, nw = words.shape
-    out = np.zeros((N, nw * 8), dtype=np.uint8)
-    for j in range(8):
-        out[:, j::8] = (words >> np.uint32(4 * j)) & np.uint32(0xF)
+    if bits == 4:
+        out = np.zeros((N, nw * 8), dtype=np.uint8)
+        for j in range(8):
+            out[:, j::8] = (words >> np.uint32(4 * j)) & np.uint32(0xF)
+        return out[:, :K]
+    assert bits == 3 and nw % 3 == 0
+    out = np.zeros((N, (nw // 3) * 32), dtype=np.uint8)
+    w64 = words.astype(np.uint64)
+    for k in range(out.shape[1]):
+        bit = 3 * k
+        w, off = bit // 32, bit % 32
+        v = w64[:, w] >> np.uint64(off)
+        if off > 29:                                            # the code continues in the next word
+            v |= w64[:, w + 1] << np.uint64(32 - off)
+        out[:, k] = (v & np.uint64(7)).astype(np.uint8)
     return out[:, :K]
 
 

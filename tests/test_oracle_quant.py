@@ -15,17 +15,19 @@ def _rand_w(N, K, seed, std=0.02):
     return (rng.standard_normal((N, K)) * std).astype(np.float32)
 
 
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,K,G", [(8, 128, 128), (5, 688, 32), (7, 256, 32), (3, 40, 16), (4, 130, 128)])
-def test_codes_are_the_nearest_representable_value(N, K, G):
+def test_codes_are_the_nearest_representable_value(N, K, G, bits):
     W = _rand_w(N, K, seed=N * 1000 + K)
-    codes, s, z = orc.quantize_rtn(W, 4, G)
-    assert codes.min() >= 0 and codes.max() <= 15
-    assert z.min() >= 0 and z.max() <= 15 and np.all(z == np.rint(z))
+    codes, s, z = orc.quantize_rtn(W, bits, G)
+    top = (1 << bits) - 1
+    assert codes.min() >= 0 and codes.max() <= top
+    assert z.min() >= 0 and z.max() <= top and np.all(z == np.rint(z))
     for n in range(N):
         for k in range(K):
             g = k // G
             sf, zz = float(s[n, g]), float(z[n, g])
-            cand = [(c - zz) * sf for c in range(16)]            # every representable value, fp64
+            cand = [(c - zz) * sf for c in range(top + 1)]       # every representable value, fp64
             err = [abs(float(W[n, k]) - v) for v in cand]
             best = min(err)
             assert err[int(codes[n, k])] <= best + 1e-6 * sf, (n, k)
@@ -97,6 +99,48 @@ def test_pack_layout_hand_written_words():
     assert words[0, 1] == 0x8000000F
     assert words[0, 2] == 0x000000A9                              # tail padded with code 0
     assert np.array_equal(orc.unpack_codes(words, 18), codes)
+
+
+def test_three_bit_pack_hand_written_words():
+    # bit stream, least-significant first: code k sits at bits 3k..3k+2 of its row
+    codes = np.array([[1, 2, 3]], dtype=np.uint8)
+    words = orc.pack_codes(codes, 3)
+    assert words.dtype == np.uint32 and words.shape == (1, 3)    # one 32-code block = 3 words
+    assert list(words[0]) == [1 + (2 << 3) + (3 << 6), 0, 0]
+    # codes 10 and 21 straddle the word boundaries (bits 30-32 and 63-65)
+    codes = np.zeros((1, 32), dtype=np.uint8)
+    codes[0, 10], codes[0, 21], codes[0, 31] = 0b110, 0b101, 0b111
+    words = orc.pack_codes(codes, 3)
+    assert list(words[0]) == [0b10 << 30, 0b1 | (0b1 << 31), 0b10 | (0b111 << 29)]
+    assert np.array_equal(orc.unpack_codes(words, 32, 3), codes)
+
+
+def test_three_bit_pack_matches_big_integer_bit_stream():
+    rng = np.random.default_rng(4)
+    for K in (32, 40, 688, 96):
+        codes = rng.integers(0, 8, size=(3, K)).astype(np.uint8)
+        words = orc.pack_codes(codes, 3)
+        assert words.shape == (3, 3 * ((K + 31) // 32))
+        for n in range(3):
+            stream = 0
+            for k in range(K):
+                stream |= int(codes[n, k]) << (3 * k)            # arbitrary-precision integer
+            want = [(stream >> (32 * w)) & 0xFFFFFFFF for w in range(words.shape[1])]
+            assert [int(v) for v in words[n]] == want
+        assert np.array_equal(orc.unpack_codes(words, K, 3), codes)
+
+
+def test_three_bit_lattice_and_one_sided_groups():
+    s0 = float(np.float16(0.031))
+    j = np.array([[0, 7, 3, 5, 1, 6, 2, 4]] * 2)
+    W = ((j - 3) * s0).astype(np.float32)
+    codes, s, z = orc.quantize_rtn(W, 3, 8)
+    assert np.all(z == 3) and np.all(codes == j)
+    Wp = np.abs(_rand_w(3, 32, 5)) + 0.01
+    codes, s, z = orc.quantize_rtn(Wp, 3, 32)
+    assert np.all(z == 0) and codes.max() == 7
+    codes, s, z = orc.quantize_rtn(-Wp, 3, 32)
+    assert np.all(z == 7) and codes.min() == 0
 
 
 def test_pack_roundtrip_ragged():
