@@ -71,12 +71,15 @@ int qtale_get_control(const qtale_ctx* ctx, int* mode /*host*/, float* value /*h
  * short): lo = min(0,min W), hi = max(0,max W), scale = fp16((hi-lo)/(2^bits-1)) (1.0 if that is 0 or
  * not finite), zero = clamp(rint(-lo/scale)), code = clamp(rint(W/scale)+zero); IEEE fp32 arithmetic,
  * round-half-even.  Dequantized weight: (code - zero) * scale.
- *   codes     [N][ceil(K/8)] uint32, nibble j of word w = code of k = 8*w + j, row tails padded with 0
+ *   codes     bits = 4: [N][ceil(K/8)] uint32, nibble j of word w = code of k = 8*w + j;
+ *             bits = 3: [N][3*ceil(K/32)] uint32, the row's codes as one little-endian bit stream, code k
+ *             at bits 3k..3k+2 (32 codes fill three words); row tails padded with code 0
  *   scales    [N][ceil(K/group)] fp16 bit patterns
  *   zeros     [N][ceil(K/group)] fp16 bit patterns of the integer zero-point
  *   prepacked the kernels' private copy (codes reordered for the matrix-core operand layout plus
  *             scale/zero pairs), qtale_prepacked_bytes() bytes, 16-byte aligned; may be NULL here.
- * Supported: bits = 4; group in {32, 64, 128}; K % 8 == 0.  Else QTALE_ERR_UNSUPPORTED / _SHAPE.
+ * Supported: bits in {4, 3} (Sec. 4.1 evaluates both); group in {32, 64, 128}; K % 8 == 0.  Else
+ * QTALE_ERR_UNSUPPORTED / _SHAPE.
  * The GEMM entry points (forward calls, qtale_linear_w4a16, qtale_swiglu_w4a16) also need N % 8 == 0. */
 size_t qtale_prepacked_bytes(int N, int K, int bits, int group);
 int qtale_quantize(const float* W, int N, int K, int bits, int group,
@@ -96,7 +99,7 @@ typedef struct {
 
 typedef struct {
     int hidden, n_heads, n_kv_heads, head_dim, inter;   /* head_dim must be 64 or 128 */
-    int bits;                                           /* 4 */
+    int bits;                                           /* 4 or 3: code width of all seven linears */
     int group;                                          /* 32, 64 or 128 */
     int act_dtype;                                      /* QTALE_ACT_FP16 | QTALE_ACT_BF16 */
     float rms_eps;                                      /* e.g. 1e-5 */
@@ -164,11 +167,12 @@ int qtale_router_select(qtale_ctx* ctx, int act_dtype, const void* x, int T, int
                         int32_t* cu_exec /*nullable [B+1]: executed tokens before each sequence*/,
                         void* stream);
 
-/* out[M][N] (fp16) = A[M][K] (fp16) x dequant(W)^T for one quantized linear (W4A16 matrix-core GEMM). */
-int qtale_linear_w4a16(const qtale_qlinear* w, int group, const void* A, int M, void* out, void* stream);
+/* out[M][N] (fp16) = A[M][K] (fp16) x dequant(W)^T for one quantized linear (matrix-core GEMM on 4-bit or
+ * 3-bit codes, `bits`/`group` as given to qtale_quantize for this matrix). */
+int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* A, int M, void* out, void* stream);
 
 /* act[M][I] (fp16) = silu(A Wgate^T) * (A Wup^T): the fused gate/up GEMM of the SwiGLU MLP. */
-int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int group,
+int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int bits, int group,
                        const void* A, int M, void* out, void* stream);
 
 /* Per-kernel timing with HIP events recorded on the forward call's stream.  While enabled, every

@@ -82,8 +82,8 @@ def load_library():
     lib.qtale_stack_forward.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, i, vp,
                                         i, vp, C.POINTER(qtale_kv), vp, vp, vp, vp, vp, sz, vp]
     lib.qtale_router_select.argtypes = [vp, i, vp, i, i, vp, f, vp, i, vp, vp, vp, vp, vp]
-    lib.qtale_linear_w4a16.argtypes = [C.POINTER(qtale_qlinear), i, vp, i, vp, vp]
-    lib.qtale_swiglu_w4a16.argtypes = [C.POINTER(qtale_qlinear), C.POINTER(qtale_qlinear), i, vp, i, vp, vp]
+    lib.qtale_linear_w4a16.argtypes = [C.POINTER(qtale_qlinear), i, i, vp, i, vp, vp]
+    lib.qtale_swiglu_w4a16.argtypes = [C.POINTER(qtale_qlinear), C.POINTER(qtale_qlinear), i, i, vp, i, vp, vp]
     lib.qtale_profile_enable.argtypes = [vp, i]
     lib.qtale_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     for name in EXPORTS:
@@ -161,12 +161,17 @@ class QuantLinear:
                              self.prepacked.data_ptr(), self.N, self.K)
 
 
+def canonical_words(K, bits):
+    """uint32 words per row of the canonical code array."""
+    return 3 * ((K + 31) // 32) if bits == 3 else (K + 7) // 8
+
+
 def qtale_quantize(W, bits=4, group=128, keep_canonical=True):
     """W: fp32 [N, K] CUDA tensor.  Returns a QuantLinear whose buffers were written by the library."""
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
     N, K = W.shape
     ng = (K + group - 1) // group
-    codes = torch.empty((N, (K + 7) // 8), dtype=torch.int32, device=W.device)
+    codes = torch.empty((N, canonical_words(K, bits)), dtype=torch.int32, device=W.device)
     scales = torch.empty((N, ng), dtype=torch.float16, device=W.device)
     zeros = torch.empty((N, ng), dtype=torch.float16, device=W.device)
     nbytes = qtale_prepacked_bytes(N, K, bits, group)
@@ -282,7 +287,7 @@ def qtale_linear_w4a16(qlin, A, out=None):
     if out is None:
         out = torch.empty((M, qlin.N), dtype=torch.float16, device=A.device)
     s = qlin.c_struct()
-    _check(load_library().qtale_linear_w4a16(C.byref(s), qlin.group, _ptr(A), M, _ptr(out), _stream()),
+    _check(load_library().qtale_linear_w4a16(C.byref(s), qlin.bits, qlin.group, _ptr(A), M, _ptr(out), _stream()),
            "qtale_linear_w4a16")
     return out
 
@@ -293,7 +298,7 @@ def qtale_swiglu_w4a16(gate, up, A, out=None):
     if out is None:
         out = torch.empty((M, gate.N), dtype=torch.float16, device=A.device)
     g, u = gate.c_struct(), up.c_struct()
-    _check(load_library().qtale_swiglu_w4a16(C.byref(g), C.byref(u), gate.group, _ptr(A), M, _ptr(out), _stream()),
+    _check(load_library().qtale_swiglu_w4a16(C.byref(g), C.byref(u), gate.bits, gate.group, _ptr(A), M, _ptr(out), _stream()),
            "qtale_swiglu_w4a16")
     return out
 

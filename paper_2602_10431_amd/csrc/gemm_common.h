@@ -10,7 +10,7 @@ struct GemmDev {
     const half_t* A;
     const int32_t* count;
     int M_max, K, KT, gshift;
-    const U4* codes[3];
+    const void* codes[3];
     const uint32_t* sz[3];
     int N[3], NF[3], npad[3], colbase[3];
     int n_w, vf_total, tiles_m, tiles_n;
@@ -19,6 +19,7 @@ struct GemmDev {
     const void* resid;
     const int32_t* idx;
     int bf16;
+    int bits;                      // 4 or 3: width of the weight codes
 };
 
 constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
@@ -71,6 +72,93 @@ __device__ __forceinline__ ScaleZero expand_sz(uint32_t raw) {
     r.Zhi = half2_t{zhi, zhi};
     return r;
 }
+
+// ---- 3-bit codes ------------------------------------------------------------------------------------
+// A lane's 32 codes of one fragment x k-tile occupy three words.  Each 16-bit half of a word holds five
+// codes at bits 0-2, 3-5, 6-8, 9-11, 12-14; pair h (codes 2h, 2h+1 of the lane, h = 0..14) sits at field
+// h%5 of word h/5, the even code in the low half and the odd one in the high half.  Pair 15 is spread over
+// the spare bits 15 / 31 of the three words (bit i of the code in word i).  OR-ing a field into 0x6400
+// gives 1024 + c, 1024 + 8c or 1024 + 64c; subtracting 1024 + z, or one FMA with 1/8 (1/64) and
+// -(128 + z) (-(16 + z)), yields c - z exactly, and the multiply by the scale rounds once.
+struct ScaleZero3 {
+    half2_t S, Z0, Z3, Z6;
+};
+__device__ __forceinline__ ScaleZero3 expand_sz3(uint32_t raw) {
+    const half2_t sz = __builtin_bit_cast(half2_t, raw);
+    ScaleZero3 r;
+    r.S = half2_t{sz[0], sz[0]};
+    const half_t z0 = sz[1] + static_cast<half_t>(1024.0f);
+    const half_t z3 = sz[1] + static_cast<half_t>(128.0f);
+    const half_t z6 = sz[1] + static_cast<half_t>(16.0f);
+    r.Z0 = half2_t{z0, z0};
+    r.Z3 = half2_t{z3, z3};
+    r.Z6 = half2_t{z6, z6};
+    return r;
+}
+
+// Pair h of the lane's tile (h must fold to a constant after unrolling).
+__device__ __forceinline__ half2_t dequant_pair3(const u32x3_t& t, int h, const ScaleZero3& s, uint32_t magic) {
+    const half2_t eighth = {static_cast<half_t>(0.125f), static_cast<half_t>(0.125f)};
+    const half2_t sixtyfourth = {static_cast<half_t>(0.015625f), static_cast<half_t>(0.015625f)};
+    if (h == 15) {
+        const uint32_t bits = ((t.x >> 15) & 0x00010001u) | ((t.y >> 14) & 0x00020002u) | ((t.z >> 13) & 0x00040004u);
+        const half2_t l = __builtin_bit_cast(half2_t, bits | magic);
+        return (l - s.Z0) * s.S;
+    }
+    const int wi = h / 5, f = h % 5;
+    const uint32_t w = wi == 0 ? t.x : wi == 1 ? t.y : t.z;
+    if (f == 0) return (__builtin_bit_cast(half2_t, and_or(w, 0x00070007u, magic)) - s.Z0) * s.S;
+    if (f == 1) return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(w, 0x00380038u, magic)), eighth, -s.Z3) * s.S;
+    if (f == 2) return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(w, 0x01c001c0u, magic)), sixtyfourth, -s.Z6) * s.S;
+    const uint32_t w9 = w >> 9;
+    if (f == 3) return (__builtin_bit_cast(half2_t, and_or(w9, 0x00070007u, magic)) - s.Z0) * s.S;
+    return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(w9, 0x00380038u, magic)), eighth, -s.Z3) * s.S;
+}
+
+// ---- the two code widths behind one interface -----------------------------------------------------------
+// WBits<BITS>: register type of a lane's packed codes for one fragment x k-tile, bytes per lane, expanded
+// scale/zero constants, the load and the dequantisation of k-step j (8 weights in operand order).
+template <int BITS>
+struct WBits;
+
+template <>
+struct WBits<4> {
+    using Tile = u32x4_t;
+    using SZ = ScaleZero;
+    static constexpr int kLaneBytes = 16;
+    static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
+        return (reinterpret_cast<const u32x4_t*>(frag_base) + static_cast<size_t>(kt) * 64)[lane];
+    }
+    static __device__ __forceinline__ SZ expand(uint32_t raw) { return expand_sz(raw); }
+    static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
+        const uint32_t w = j == 0 ? t.x : j == 1 ? t.y : j == 2 ? t.z : t.w;
+        return dequant8(w, s.S, s.Zlo, s.Zhi, magic);
+    }
+};
+
+template <>
+struct WBits<3> {
+    using Tile = u32x3_t;
+    using SZ = ScaleZero3;
+    static constexpr int kLaneBytes = 12;
+    static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(frag_base) + (static_cast<size_t>(kt) * 64 + lane) * 3;
+        Tile t;
+        t.x = p[0]; t.y = p[1]; t.z = p[2];
+        return t;
+    }
+    static __device__ __forceinline__ SZ expand(uint32_t raw) { return expand_sz3(raw); }
+    static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
+        const half2_t p0 = dequant_pair3(t, 4 * j + 0, s, magic);
+        const half2_t p1 = dequant_pair3(t, 4 * j + 1, s, magic);
+        const half2_t p2 = dequant_pair3(t, 4 * j + 2, s, magic);
+        const half2_t p3 = dequant_pair3(t, 4 * j + 3, s, magic);
+        half8_t r;
+        r[0] = p0[0]; r[1] = p0[1]; r[2] = p1[0]; r[3] = p1[1];
+        r[4] = p2[0]; r[5] = p2[1]; r[6] = p3[0]; r[7] = p3[1];
+        return r;
+    }
+};
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 

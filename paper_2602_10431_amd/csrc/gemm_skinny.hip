@@ -1,4 +1,4 @@
-// Skinny W4A16 GEMM for decode steps: at most 64 executed rows, so the linears stream their weights once
+// Skinny W4A16 / W3A16 GEMM for decode steps: at most 64 executed rows, so the linears stream their weights once
 // and the question is bandwidth and latency, not matrix-core throughput (Sec. 4.1 weights; the executed
 // rows come from the gather of App. B.2).
 //
@@ -8,7 +8,7 @@
 //   * a workgroup owns NFB consecutive 32-column fragments and ALL of K; its NW waves split K by
 //     interleaving k-tiles (wave w takes tiles w, w+NW, ...), each wave keeping its own accumulators for
 //     all NFB fragments, so its A registers are reused NFB times;
-//   * per tile a wave issues NFB 16-byte weight loads (1 KB each, contiguous in the prepacked layout),
+//   * per tile a wave issues NFB 16-byte (3-bit codes: 12-byte) weight loads, contiguous in the prepacked layout,
 //     the scale/zero words and its A tile (row-contiguous loads, re-laid out through a wave-private LDS
 //     region); the weights are prefetched four tiles ahead and the activations two;
 //   * the K-split partial sums meet once, at the end: every wave writes its accumulators as a [64][cols]
@@ -19,9 +19,10 @@
 
 namespace qtale {
 
-template <int NFB, int NW, int MF, int GPT, int EPI, bool RAGGED>
+template <int BITS, int NFB, int NW, int MF, int GPT, int EPI, bool RAGGED>
 __global__ void __launch_bounds__(NW * 64, (NW <= 4 ? 2 : 1))
 gemm_skinny_kernel(GemmDev p) {
+    using WB = WBits<BITS>;
     constexpr int NT = NW * 64;
     constexpr int CW = NFB * 32;                 // accumulator columns per wave
     constexpr int CSTR = CW + 4;                 // slab row stride (floats)
@@ -41,7 +42,7 @@ gemm_skinny_kernel(GemmDev p) {
     const uint32_t magic = dequant_magic();
     const int tile_n = blockIdx.x;
 
-    const u32x4_t* bbase[NFB];
+    const char* bbase[NFB];
     const uint32_t* sbase[NFB];
     int npad[NFB];
 #pragma unroll
@@ -50,7 +51,7 @@ gemm_skinny_kernel(GemmDev p) {
         if (vf >= p.vf_total) vf = p.vf_total - 1;
         int mat, f;
         map_fragment<EPI>(p, vf, mat, f);
-        bbase[fn] = reinterpret_cast<const u32x4_t*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * 64;
+        bbase[fn] = reinterpret_cast<const char*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * (64 * WB::kLaneBytes);
         sbase[fn] = p.sz[mat] + f * 32;
         npad[fn] = p.npad[mat];
     }
@@ -82,13 +83,13 @@ gemm_skinny_kernel(GemmDev p) {
     // in registers.  Loads past the wave's last tile are clamped to it (harmless, never consumed) so that
     // the load order in the loop is unconditional.
     constexpr int BD = NW <= 8 ? 4 : 2;           // weight tiles in flight per wave
-    u32x4_t bq[BD][NFB];
+    typename WB::Tile bq[BD][NFB];
     uint32_t bsz[BD][NFB][GPT];
     u32x4_t areg[AD][A_LD];
-    auto fetch_b = [&](int kt, u32x4_t* q, uint32_t (*sz)[GPT]) {
+    auto fetch_b = [&](int kt, typename WB::Tile* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < NFB; ++fn) {
-            q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
+            q[fn] = WB::load(bbase[fn], kt, lane);
 #pragma unroll
             for (int g = 0; g < GPT; ++g) {
                 const int gi = (kt * 64 + g * 32) >> p.gshift;
@@ -111,13 +112,13 @@ gemm_skinny_kernel(GemmDev p) {
 #pragma unroll
         for (int it = 0; it < A_LD; ++it) *reinterpret_cast<u32x4_t*>(dst + it * 8 * ASTR) = ar[it];
     };
-    auto compute = [&](const u32x4_t* q, const uint32_t (*szr)[GPT], int slot) {
+    auto compute = [&](const typename WB::Tile* q, const uint32_t (*szr)[GPT], int slot) {
         const half_t* src = stage_base + slot * (ROWS * ASTR) + st_r;
-        ScaleZero sz[NFB][GPT];
+        typename WB::SZ sz[NFB][GPT];
 #pragma unroll
         for (int fn = 0; fn < NFB; ++fn)
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(szr[fn][g]);
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = WB::expand(szr[fn][g]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             half8_t a[MF];
@@ -125,9 +126,7 @@ gemm_skinny_kernel(GemmDev p) {
             for (int mf = 0; mf < MF; ++mf) a[mf] = *reinterpret_cast<const half8_t*>(src + mf * 32 * ASTR + j * 16);
 #pragma unroll
             for (int fn = 0; fn < NFB; ++fn) {
-                const uint32_t wj = j == 0 ? q[fn].x : j == 1 ? q[fn].y : j == 2 ? q[fn].z : q[fn].w;
-                const ScaleZero& s = sz[fn][GPT == 2 ? (j >> 1) : 0];
-                const half8_t b = dequant8(wj, s.S, s.Zlo, s.Zhi, magic);
+                const half8_t b = WB::dequant(q[fn], j, sz[fn][GPT == 2 ? (j >> 1) : 0], magic);
 #pragma unroll
                 for (int mf = 0; mf < MF; ++mf)
                     acc[mf][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mf], b, acc[mf][fn], 0, 0, 0);
@@ -225,50 +224,54 @@ gemm_skinny_kernel(GemmDev p) {
     }
 }
 
-template <int NFB, int NW, int MF, int GPT, int EPI>
+template <int BITS, int NFB, int NW, int MF, int GPT, int EPI>
 static hipError_t launch_one(GemmDev& d, hipStream_t stream) {
     const int blocks = (d.vf_total + NFB - 1) / NFB;
     if (blocks == 0) return hipSuccess;
     if (d.K % 64 != 0)
-        hipLaunchKernelGGL((gemm_skinny_kernel<NFB, NW, MF, GPT, EPI, true>), dim3(blocks), dim3(NW * 64), 0, stream, d);
+        hipLaunchKernelGGL((gemm_skinny_kernel<BITS, NFB, NW, MF, GPT, EPI, true>), dim3(blocks), dim3(NW * 64), 0, stream, d);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<NFB, NW, MF, GPT, EPI, false>), dim3(blocks), dim3(NW * 64), 0, stream, d);
+        hipLaunchKernelGGL((gemm_skinny_kernel<BITS, NFB, NW, MF, GPT, EPI, false>), dim3(blocks), dim3(NW * 64), 0, stream, d);
     return hipGetLastError();
 }
 
-template <int GPT, int EPI>
+template <int BITS, int GPT, int EPI>
 static hipError_t launch_shape(GemmDev& d, hipStream_t stream) {
     // Pick the split so that one round of workgroups covers the chip: very wide outputs (gate/up) use four
     // waves per workgroup and two workgroups per CU, wide ones eight waves, narrow ones (few fragments)
     // one fragment per workgroup and 16 K-slices so that more CUs take part.
     if (EPI == EPI_SWIGLU_F16 || d.vf_total >= 512) {
-        if (d.M_max <= 32) return launch_one<2, 4, 1, GPT, EPI>(d, stream);
-        return launch_one<2, 4, 2, GPT, EPI>(d, stream);
+        if (d.M_max <= 32) return launch_one<BITS, 2, 4, 1, GPT, EPI>(d, stream);
+        return launch_one<BITS, 2, 4, 2, GPT, EPI>(d, stream);
     }
     if (d.vf_total >= 256) {
-        if (d.M_max <= 32) return launch_one<2, 8, 1, GPT, EPI>(d, stream);
-        return launch_one<2, 8, 2, GPT, EPI>(d, stream);
+        if (d.M_max <= 32) return launch_one<BITS, 2, 8, 1, GPT, EPI>(d, stream);
+        return launch_one<BITS, 2, 8, 2, GPT, EPI>(d, stream);
     }
     if constexpr (EPI != EPI_SWIGLU_F16) {
-        if (d.M_max <= 32) return launch_one<1, 16, 1, GPT, EPI>(d, stream);
-        return launch_one<1, 16, 2, GPT, EPI>(d, stream);
+        if (d.M_max <= 32) return launch_one<BITS, 1, 16, 1, GPT, EPI>(d, stream);
+        return launch_one<BITS, 1, 16, 2, GPT, EPI>(d, stream);
     }
     return hipErrorInvalidValue;       // SwiGLU always takes the first branch
 }
 
-template <int GPT>
+template <int BITS, int GPT>
 static hipError_t launch_gpt(GemmDev& d, int epi, hipStream_t stream) {
     switch (epi) {
-        case EPI_STORE_F16: return launch_shape<GPT, EPI_STORE_F16>(d, stream);
-        case EPI_RESID_F32: return launch_shape<GPT, EPI_RESID_F32>(d, stream);
-        case EPI_SWIGLU_F16: return launch_shape<GPT, EPI_SWIGLU_F16>(d, stream);
-        default: return launch_shape<GPT, EPI_RESID_SCATTER>(d, stream);
+        case EPI_STORE_F16: return launch_shape<BITS, GPT, EPI_STORE_F16>(d, stream);
+        case EPI_RESID_F32: return launch_shape<BITS, GPT, EPI_RESID_F32>(d, stream);
+        case EPI_SWIGLU_F16: return launch_shape<BITS, GPT, EPI_SWIGLU_F16>(d, stream);
+        default: return launch_shape<BITS, GPT, EPI_RESID_SCATTER>(d, stream);
     }
 }
 
 hipError_t launch_gemm_skinny(GemmDev& d, int epilogue, hipStream_t stream) {
-    if (d.gshift == 5) return launch_gpt<2>(d, epilogue, stream);
-    return launch_gpt<1>(d, epilogue, stream);
+    if (d.bits == 3) {
+        if (d.gshift == 5) return launch_gpt<3, 2>(d, epilogue, stream);
+        return launch_gpt<3, 1>(d, epilogue, stream);
+    }
+    if (d.gshift == 5) return launch_gpt<4, 2>(d, epilogue, stream);
+    return launch_gpt<4, 1>(d, epilogue, stream);
 }
 
 }  // namespace qtale

@@ -1,5 +1,6 @@
-// W4A16 GEMM for the layer's linears on the compacted tokens: C[M][N] = A[M][K] (fp16) x W'[N][K]^T,
-// W' = (code - zero) * scale per group of the input dimension (Sec. 4.1 weight-only group quantization).
+// W4A16 / W3A16 GEMM for the layer's linears on the compacted tokens: C[M][N] = A[M][K] (fp16) x W'[N][K]^T,
+// W' = (code - zero) * scale per group of the input dimension (Sec. 4.1 weight-only group quantization,
+// 4-bit and 3-bit codes).
 //
 // Design for gfx950 (64-wide waves, v_mfma_f32_32x32x16_f16, 160 KB LDS):
 //   * Weights are the B operand.  In the prepacked layout one 16-byte load gives a lane the 4 x 8 codes
@@ -20,9 +21,10 @@
 
 namespace qtale {
 
-template <int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED>
+template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED>
 __global__ void __launch_bounds__(WM * WN * 64, OCC)
 gemm_w4a16_kernel(GemmDev p) {
+    using WB = WBits<BITS>;
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * FM * 32;
     constexpr int A_LOADS = (BM * 8) / NT;
@@ -51,7 +53,7 @@ gemm_w4a16_kernel(GemmDev p) {
     const uint32_t magic = dequant_magic();
 
     // ---- which weight fragments this wave owns (all wave-uniform -> scalar base addresses) ------
-    const u32x4_t* bbase[FN];
+    const char* bbase[FN];
     const uint32_t* sbase[FN];
     int npad[FN];
 #pragma unroll
@@ -68,7 +70,7 @@ gemm_w4a16_kernel(GemmDev p) {
             if (p.n_w > 1 && f >= p.NF[0]) { f -= p.NF[0]; mat = 1; }
             if (p.n_w > 2 && mat == 1 && f >= p.NF[1]) { f -= p.NF[1]; mat = 2; }
         }
-        bbase[fn] = reinterpret_cast<const u32x4_t*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * 64;
+        bbase[fn] = reinterpret_cast<const char*>(p.codes[mat]) + static_cast<size_t>(f) * p.KT * (64 * WB::kLaneBytes);
         sbase[fn] = p.sz[mat] + f * 32;
         npad[fn] = p.npad[mat];
     }
@@ -113,12 +115,12 @@ gemm_w4a16_kernel(GemmDev p) {
         for (int it = 0; it < A_LOADS; ++it) *reinterpret_cast<u32x4_t*>(&As[buf][a_dst[it]]) = areg[it];
     };
 
-    u32x4_t bq[2][FN];                   // packed codes of the current / next k-tile (ping-pong)
+    typename WB::Tile bq[2][FN];         // packed codes of the current / next k-tile (ping-pong)
     uint32_t bsz[2][FN][GPT];       // their scale|zero words
-    auto load_b = [&](int kt, u32x4_t* q, uint32_t (*sz)[GPT]) {
+    auto load_b = [&](int kt, typename WB::Tile* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) {
-            q[fn] = (bbase[fn] + static_cast<size_t>(kt) * 64)[lane];
+            q[fn] = WB::load(bbase[fn], kt, lane);
 #pragma unroll
             for (int g = 0; g < GPT; ++g) {
                 const int gi = (kt * 64 + g * 32) >> p.gshift;
@@ -160,17 +162,14 @@ gemm_w4a16_kernel(GemmDev p) {
     for (int kt = 0; kt < p.KT; ++kt) {
         const int nbuf = buf == NBUF - 1 ? 0 : buf + 1;
         load_b(min(kt + 1, last), bq[1], bsz[1]);
-        ScaleZero sz[FN][GPT];
+        typename WB::SZ sz[FN][GPT];
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[fn][g] = expand_sz(bsz[0][fn][g]);
-        auto wsel = [&](int fn, int j) {
-            return j == 0 ? bq[0][fn].x : j == 1 ? bq[0][fn].y : j == 2 ? bq[0][fn].z : bq[0][fn].w;
-        };
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = WB::expand(bsz[0][fn][g]);
         const half_t* Ab = &As[buf][a_row0];
         const half_t* An = &As[nbuf][a_row0];
-        half8_t bcur = dequant8(wsel(0, 0), sz[0][0].S, sz[0][0].Zlo, sz[0][0].Zhi, magic);
+        half8_t bcur = WB::dequant(bq[0][0], 0, sz[0][0], magic);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j == 1) {
@@ -187,8 +186,7 @@ gemm_w4a16_kernel(GemmDev p) {
                 const int jn = fn + 1 < FN ? j : j + 1;
                 half8_t bnext = bcur;
                 if (jn < 4) {
-                    const ScaleZero& sn = sz[fnn][GPT == 2 ? (jn >> 1) : 0];
-                    bnext = dequant8(wsel(fnn, jn), sn.S, sn.Zlo, sn.Zhi, magic);
+                    bnext = WB::dequant(bq[0][fnn], jn, sz[fnn][GPT == 2 ? (jn >> 1) : 0], magic);
                 }
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
@@ -302,7 +300,7 @@ gemm_w4a16_kernel(GemmDev p) {
     }
 }
 
-template <int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC>
+template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC>
 static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     constexpr int BM = WM * FM * 32;
     constexpr int BNF = WN * FN;
@@ -311,24 +309,24 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     const int blocks = d.tiles_m * d.tiles_n;
     if (blocks == 0) return hipSuccess;
     if (d.K % 64 != 0)
-        hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI, OCC, true>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+        hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, true>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
     else
-        hipLaunchKernelGGL((gemm_w4a16_kernel<WM, WN, FM, FN, GPT, EPI, OCC, false>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+        hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, false>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
     return hipGetLastError();
 }
 
-template <int GPT, int EPI>
+template <int BITS, int GPT, int EPI>
 static hipError_t launch_epi(GemmDev& d, hipStream_t stream) {
-    return launch_cfg<1, 4, 4, 2, GPT, EPI, 2>(d, stream);
+    return launch_cfg<BITS, 1, 4, 4, 2, GPT, EPI, 2>(d, stream);
 }
 
-template <int GPT>
+template <int BITS, int GPT>
 static hipError_t launch_gpt(GemmDev& d, int epi, hipStream_t stream) {
     switch (epi) {
-        case EPI_STORE_F16: return launch_epi<GPT, EPI_STORE_F16>(d, stream);
-        case EPI_RESID_F32: return launch_epi<GPT, EPI_RESID_F32>(d, stream);
-        case EPI_SWIGLU_F16: return launch_epi<GPT, EPI_SWIGLU_F16>(d, stream);
-        default: return launch_epi<GPT, EPI_RESID_SCATTER>(d, stream);
+        case EPI_STORE_F16: return launch_epi<BITS, GPT, EPI_STORE_F16>(d, stream);
+        case EPI_RESID_F32: return launch_epi<BITS, GPT, EPI_RESID_F32>(d, stream);
+        case EPI_SWIGLU_F16: return launch_epi<BITS, GPT, EPI_SWIGLU_F16>(d, stream);
+        default: return launch_epi<BITS, GPT, EPI_RESID_SCATTER>(d, stream);
     }
 }
 
@@ -345,8 +343,8 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     int col = 0, vf = 0;
     for (int i = 0; i < 3; ++i) {
         const int j = i < a.n_w ? i : 0;
-        const PrepackDims pd = prepack_dims(a.w[j].N, a.w[j].K, a.group);
-        d.codes[i] = reinterpret_cast<const U4*>(a.w[j].prepacked);
+        const PrepackDims pd = prepack_dims(a.w[j].N, a.w[j].K, a.group, a.bits);
+        d.codes[i] = a.w[j].prepacked;
         d.sz[i] = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(a.w[j].prepacked) + pd.code_bytes);
         d.N[i] = a.w[j].N;
         d.NF[i] = pd.NF;
@@ -360,9 +358,14 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     d.resid = a.resid;
     d.idx = a.idx;
     d.bf16 = a.bf16;
+    d.bits = a.bits;
     if (d.M_max <= 64) return launch_gemm_skinny(d, a.epilogue, stream);
-    if (a.group == 32) return launch_gpt<2>(d, a.epilogue, stream);
-    return launch_gpt<1>(d, a.epilogue, stream);
+    if (a.bits == 3) {
+        if (a.group == 32) return launch_gpt<3, 2>(d, a.epilogue, stream);
+        return launch_gpt<3, 1>(d, a.epilogue, stream);
+    }
+    if (a.group == 32) return launch_gpt<4, 2>(d, a.epilogue, stream);
+    return launch_gpt<4, 1>(d, a.epilogue, stream);
 }
 
 }  // namespace qtale

@@ -75,7 +75,7 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
 
 int check_quant_params(int N, int K, int bits, int group) {
     if (N <= 0 || K <= 0) return QTALE_ERR_INVALID_ARG;
-    if (bits != 4) return QTALE_ERR_UNSUPPORTED;
+    if (bits != 4 && bits != 3) return QTALE_ERR_UNSUPPORTED;
     if (group != 32 && group != 64 && group != 128) return QTALE_ERR_UNSUPPORTED;
     if (K % 8 != 0) return QTALE_ERR_SHAPE;
     return QTALE_OK;
@@ -85,7 +85,7 @@ int check_cfg(const qtale_layer_cfg* c) {
     if (!c) return QTALE_ERR_INVALID_ARG;
     if (c->hidden <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->inter <= 0)
         return QTALE_ERR_INVALID_ARG;
-    if (c->bits != 4) return QTALE_ERR_UNSUPPORTED;
+    if (c->bits != 4 && c->bits != 3) return QTALE_ERR_UNSUPPORTED;
     if (c->group != 32 && c->group != 64 && c->group != 128) return QTALE_ERR_UNSUPPORTED;
     if (c->head_dim != 64 && c->head_dim != 128) return QTALE_ERR_UNSUPPORTED;
     if (c->act_dtype != QTALE_ACT_FP16 && c->act_dtype != QTALE_ACT_BF16) return QTALE_ERR_UNSUPPORTED;
@@ -204,7 +204,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 3);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.n_w = 3;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 3;
         g.w[0] = {w->q.prepacked, w->q.N, w->q.K};
         g.w[1] = {w->k.prepacked, w->k.N, w->k.K};
         g.w[2] = {w->v.prepacked, w->v.N, w->v.K};
@@ -232,7 +232,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 6);
         GemmArgs g{};
-        g.A = ws.attn; g.count = count; g.M_max = M_max; g.K = nh * d; g.group = c->group; g.n_w = 1;
+        g.A = ws.attn; g.count = count; g.M_max = M_max; g.K = nh * d; g.group = c->group; g.bits = c->bits; g.n_w = 1;
         g.w[0] = {w->o.prepacked, w->o.N, w->o.K};
         g.epilogue = EPI_RESID_F32; g.out = ws.h; g.ldo = H; g.resid = x; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));
@@ -244,7 +244,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 8);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.n_w = 2;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 2;
         g.w[0] = {w->gate.prepacked, w->gate.N, w->gate.K};
         g.w[1] = {w->up.prepacked, w->up.N, w->up.K};
         g.epilogue = EPI_SWIGLU_F16; g.out = ws.act; g.ldo = I;
@@ -253,7 +253,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 9);
         GemmArgs g{};
-        g.A = ws.act; g.count = count; g.M_max = M_max; g.K = I; g.group = c->group; g.n_w = 1;
+        g.A = ws.act; g.count = count; g.M_max = M_max; g.K = I; g.group = c->group; g.bits = c->bits; g.n_w = 1;
         g.w[0] = {w->down.prepacked, w->down.N, w->down.K};
         g.epilogue = EPI_RESID_SCATTER; g.out = x; g.ldo = H; g.resid = ws.h; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));
@@ -334,7 +334,7 @@ int qtale_get_control(const qtale_ctx* ctx, int* mode, float* value) {
 
 size_t qtale_prepacked_bytes(int N, int K, int bits, int group) {
     if (check_quant_params(N, K, bits, group) != QTALE_OK) return 0;
-    const PrepackDims d = prepack_dims(N, K, group);
+    const PrepackDims d = prepack_dims(N, K, group, bits);
     return d.code_bytes + d.sz_bytes;
 }
 
@@ -346,7 +346,7 @@ int qtale_quantize(const float* W, int N, int K, int bits, int group, uint32_t* 
     if (prepacked && reinterpret_cast<uintptr_t>(prepacked) % 16 != 0) return QTALE_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     HIP_TRY(launch_quantize(W, N, K, bits, group, codes, scales, zeros, s));
-    if (prepacked) HIP_TRY(launch_prepack(codes, scales, zeros, N, K, group, prepacked, s));
+    if (prepacked) HIP_TRY(launch_prepack(codes, scales, zeros, N, K, bits, group, prepacked, s));
     return QTALE_OK;
 }
 
@@ -356,7 +356,7 @@ int qtale_prepack(const uint32_t* codes, const uint16_t* scales, const uint16_t*
     if (e) return e;
     if (!codes || !scales || !zeros || !prepacked) return QTALE_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(prepacked) % 16 != 0) return QTALE_ERR_INVALID_ARG;
-    HIP_TRY(launch_prepack(codes, scales, zeros, N, K, group, prepacked, reinterpret_cast<hipStream_t>(stream)));
+    HIP_TRY(launch_prepack(codes, scales, zeros, N, K, bits, group, prepacked, reinterpret_cast<hipStream_t>(stream)));
     return QTALE_OK;
 }
 
@@ -433,31 +433,31 @@ int qtale_router_select(qtale_ctx* ctx, int act_dtype, const void* x, int T, int
     return QTALE_OK;
 }
 
-int qtale_linear_w4a16(const qtale_qlinear* w, int group, const void* A, int M, void* out, void* stream) {
+int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* A, int M, void* out, void* stream) {
     if (!w || M < 0) return QTALE_ERR_INVALID_ARG;
-    int e = check_quant_params(w->N, w->K, 4, group);
+    int e = check_quant_params(w->N, w->K, bits, group);
     if (e) return e;
     if (w->N % 8 != 0) return QTALE_ERR_SHAPE;
     if (M == 0) return QTALE_OK;
     if (!w->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
-    g.A = A; g.M_max = M; g.K = w->K; g.group = group; g.n_w = 1;
+    g.A = A; g.M_max = M; g.K = w->K; g.group = group; g.bits = bits; g.n_w = 1;
     g.w[0] = {w->prepacked, w->N, w->K};
     g.epilogue = EPI_STORE_F16; g.out = out; g.ldo = w->N;
     HIP_TRY(launch_gemm_w4a16(g, reinterpret_cast<hipStream_t>(stream)));
     return QTALE_OK;
 }
 
-int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int group, const void* A, int M,
+int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int bits, int group, const void* A, int M,
                        void* out, void* stream) {
     if (!gate || !up || M < 0) return QTALE_ERR_INVALID_ARG;
-    int e = check_quant_params(gate->N, gate->K, 4, group);
+    int e = check_quant_params(gate->N, gate->K, bits, group);
     if (e) return e;
     if (gate->N != up->N || gate->K != up->K || gate->N % 8 != 0) return QTALE_ERR_SHAPE;
     if (M == 0) return QTALE_OK;
     if (!gate->prepacked || !up->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
-    g.A = A; g.M_max = M; g.K = gate->K; g.group = group; g.n_w = 2;
+    g.A = A; g.M_max = M; g.K = gate->K; g.group = group; g.bits = bits; g.n_w = 2;
     g.w[0] = {gate->prepacked, gate->N, gate->K};
     g.w[1] = {up->prepacked, up->N, up->K};
     g.epilogue = EPI_SWIGLU_F16; g.out = out; g.ldo = gate->N;

@@ -10,12 +10,12 @@ struct PrepackDims {
     int NF, KT, NGP;
     size_t code_bytes, sz_bytes;
 };
-PrepackDims prepack_dims(int N, int K, int group);
+PrepackDims prepack_dims(int N, int K, int group, int bits);
 
 hipError_t launch_quantize(const float* W, int N, int K, int bits, int group, uint32_t* codes,
                            uint16_t* scales, uint16_t* zeros, hipStream_t stream);
 hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const uint16_t* zeros, int N,
-                          int K, int group, void* prepacked, hipStream_t stream);
+                          int K, int bits, int group, void* prepacked, hipStream_t stream);
 
 // ---- router + selection --------------------------------------------------------------------
 hipError_t launch_router_score(const void* x, int bf16, int T, int H, const float* w, float b,
@@ -62,7 +62,7 @@ struct RopeArgs {
 };
 hipError_t launch_rope_append(const RopeArgs& a, hipStream_t stream);
 
-// ---- W4A16 GEMM ---------------------------------------------------------------------------------
+// ---- W4A16 / W3A16 GEMM ---------------------------------------------------------------------------------
 enum GemmEpilogue { EPI_STORE_F16 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU_F16 = 2, EPI_RESID_SCATTER = 3 };
 
 struct GemmWeights {
@@ -76,6 +76,7 @@ struct GemmArgs {
     int M_max;                 // host upper bound of rows (grid size)
     int K;
     int group;
+    int bits;                  // 4 or 3
     int n_w;                   // number of weight matrices: 1, 2 (gate/up interleaved), 3 (q|k|v concatenated)
     GemmWeights w[3];
     int epilogue;

@@ -1,6 +1,7 @@
-// Group-wise round-to-nearest int4 quantizer and the matrix-core prepack (setup step, off the timed path).
+// Group-wise round-to-nearest int4 / int3 quantizer and the matrix-core prepack (setup step, off the timed
+// path).
 //
-// Sec. 4.1 of the paper fixes "weight-only, group size 128, 4 bit"; the arithmetic below is this
+// Sec. 4.1 of the paper fixes "weight-only, group size 128, 4 and 3 bit"; the arithmetic below is this
 // library's reading: asymmetric min/max with zero inside the range, fp16 scale, integer zero-point,
 // IEEE fp32 operations with round-half-even so that the codes are reproducible bit for bit.
 #include "qtale_dev.h"
@@ -8,10 +9,13 @@
 
 namespace qtale {
 
-// One thread owns 8 consecutive k of one row (one canonical uint32 word).  The group/8 threads of a
-// group are consecutive lanes of one wave and reduce min/max with xor-shuffles.
+// One thread owns 8 consecutive k of one row (one canonical uint32 word of 4-bit codes, or 24 bits of the
+// 3-bit stream).  The group/8 threads of a group are consecutive lanes of one wave and reduce min/max
+// with xor-shuffles.  3-bit codes: four consecutive threads hold one 32-code block = 96 bits = 3 words of
+// the row's little-endian bit stream (code k at bits 3k..3k+2); they exchange their 24-bit pieces with
+// shuffles and the first three write one word each.
 __global__ void __launch_bounds__(256)
-quantize_rows_kernel(const float* __restrict__ W, int N, int K, int group, int n_groups, float qmax,
+quantize_rows_kernel(const float* __restrict__ W, int N, int K, int bits, int group, int n_groups, float qmax,
                      uint32_t* __restrict__ codes, uint16_t* __restrict__ scales, uint16_t* __restrict__ zeros) {
     const int wpg = group >> 3;                       // words (threads) per group: 4, 8 or 16
     const int wpr = n_groups * wpg;                   // padded words per row
@@ -37,23 +41,33 @@ quantize_rows_kernel(const float* __restrict__ W, int N, int K, int group, int n
         lo = fminf(lo, __shfl_xor(lo, o, 64));
         hi = fmaxf(hi, __shfl_xor(hi, o, 64));
     }
-    if (!ok) return;
     lo = fminf(lo, 0.0f);
     hi = fmaxf(hi, 0.0f);
-    const float s32 = __fdiv_rn(__fsub_rn(hi, lo), qmax);
+    const float s32 = __fdiv_rn(__fsub_rn(hi, lo), qmax);     // lanes outside the matrix see lo = hi = 0 here
     half_t s16 = static_cast<half_t>(s32);                                   // round to nearest even
     float sf = static_cast<float>(s16);
     if (sf == 0.0f || !(fabsf(sf) <= 65504.0f)) { s16 = static_cast<half_t>(1.0f); sf = 1.0f; }
     const float z = fminf(fmaxf(rintf(__fdiv_rn(-lo, sf)), 0.0f), qmax);
     uint32_t word = 0;
+    if (ok) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float q = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(v[i], sf)), z), 0.0f), qmax);
-        word |= static_cast<uint32_t>(q) << (4 * i);
+        for (int i = 0; i < 8; ++i) {
+            const float q = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(v[i], sf)), z), 0.0f), qmax);
+            word |= static_cast<uint32_t>(q) << (bits * i);
+        }
     }
-    const int kw = (K + 7) >> 3;
-    codes[static_cast<size_t>(n) * kw + w] = word;
-    if ((w % wpg) == 0) {
+    if (bits == 3) {                                  // uniform branch: every lane of the wave takes part
+        const int lane = threadIdx.x & 63, q0 = lane & ~3, i = lane & 3;
+        const uint32_t v0 = __shfl(word, q0, 64), v1 = __shfl(word, q0 + 1, 64);
+        const uint32_t v2 = __shfl(word, q0 + 2, 64), v3 = __shfl(word, q0 + 3, 64);
+        const uint32_t out = i == 0 ? (v0 | (v1 << 24)) : i == 1 ? ((v1 >> 8) | (v2 << 16)) : ((v2 >> 16) | (v3 << 8));
+        const int blk = w >> 2;                       // 32-code block of the row; its first thread has k0 = 32*blk
+        if (row_ok && i < 3 && blk * 32 < K)
+            codes[static_cast<size_t>(n) * (3 * ((K + 31) >> 5)) + 3 * blk + i] = out;
+    } else if (ok) {
+        codes[static_cast<size_t>(n) * ((K + 7) >> 3) + w] = word;
+    }
+    if (ok && (w % wpg) == 0) {
         const int g = w / wpg;
         scales[static_cast<size_t>(n) * n_groups + g] = __builtin_bit_cast(uint16_t, s16);
         zeros[static_cast<size_t>(n) * n_groups + g] = __builtin_bit_cast(uint16_t, static_cast<half_t>(z));
@@ -121,12 +135,73 @@ prepack_kernel(const uint32_t* __restrict__ codes, const uint16_t* __restrict__ 
     }
 }
 
-PrepackDims prepack_dims(int N, int K, int group) {
+// 3-bit codes.  Same fragment / k-tile order, 12 bytes per lane: the lane's 32 codes q = 8 j + e (k-step j,
+// element e, k = 64 kt + 16 j + 8 (l/32) + e) form 16 pairs h = q/2; pair h < 15 sits in word h/5 at bit
+// 3*(h%5) of the low half (even code) and of the high half (odd code); pair 15 is spread over the spare
+// bits 15 (even code) and 31 (odd code) of the three words, bit i of the code in word i.  sz as above.
+__global__ void __launch_bounds__(256)
+prepack3_kernel(const uint32_t* __restrict__ codes, const uint16_t* __restrict__ scales,
+                const uint16_t* __restrict__ zeros, int N, int K, int group, int n_groups,
+                int NF, int KT, int NGP, uint32_t* __restrict__ pcodes, uint32_t* __restrict__ psz) {
+    const long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const long n_code = static_cast<long>(NF) * KT * 64;
+    const int kw = 3 * ((K + 31) >> 5);
+    if (gid < n_code) {
+        const int lane = static_cast<int>(gid & 63);
+        const long t = gid >> 6;
+        const int kt = static_cast<int>(t % KT);
+        const int f = static_cast<int>(t / KT);
+        const int n = f * 32 + (lane & 31);
+        uint32_t out[3] = {0u, 0u, 0u};
+        for (int q = 0; q < 32; ++q) {
+            const int k = kt * 64 + (q >> 3) * 16 + (lane >> 5) * 8 + (q & 7);
+            uint32_t c = 0;
+            if (n < N) {
+                if (k < K) {
+                    const uint32_t* row = codes + static_cast<size_t>(n) * kw;
+                    const int bit = 3 * k, wi = bit >> 5, off = bit & 31;
+                    uint32_t v = row[wi] >> off;
+                    if (off > 29) v |= row[wi + 1] << (32 - off);
+                    c = v & 7u;
+                } else {
+                    const int g = k / group;
+                    c = g < n_groups
+                        ? static_cast<uint32_t>(static_cast<float>(__builtin_bit_cast(half_t, zeros[static_cast<size_t>(n) * n_groups + g])))
+                        : 0u;
+                }
+            }
+            const int h = q >> 1, hs = (q & 1) * 16;
+            if (h < 15) {
+                out[h / 5] |= c << (3 * (h % 5) + hs);
+            } else {
+                out[0] |= (c & 1u) << (15 + hs);
+                out[1] |= ((c >> 1) & 1u) << (15 + hs);
+                out[2] |= ((c >> 2) & 1u) << (15 + hs);
+            }
+        }
+        pcodes[gid * 3 + 0] = out[0];
+        pcodes[gid * 3 + 1] = out[1];
+        pcodes[gid * 3 + 2] = out[2];
+    }
+    const long n_sz = static_cast<long>(NGP) * NF * 32;
+    if (gid < n_sz) {
+        const int n = static_cast<int>(gid % (NF * 32));
+        const int g = static_cast<int>(gid / (NF * 32));
+        uint32_t v = 0;
+        if (n < N && g < n_groups) {
+            v = static_cast<uint32_t>(scales[static_cast<size_t>(n) * n_groups + g]) |
+                (static_cast<uint32_t>(zeros[static_cast<size_t>(n) * n_groups + g]) << 16);
+        }
+        psz[gid] = v;
+    }
+}
+
+PrepackDims prepack_dims(int N, int K, int group, int bits) {
     PrepackDims d;
     d.NF = (N + 31) / 32;
     d.KT = (K + 63) / 64;
     d.NGP = (d.KT * 64 + group - 1) / group;
-    d.code_bytes = static_cast<size_t>(d.NF) * d.KT * 1024;
+    d.code_bytes = static_cast<size_t>(d.NF) * d.KT * (bits == 3 ? 768 : 1024);
     d.sz_bytes = static_cast<size_t>(d.NGP) * d.NF * 32 * 4;
     return d;
 }
@@ -137,14 +212,14 @@ hipError_t launch_quantize(const float* W, int N, int K, int bits, int group, ui
     const long total = static_cast<long>(N) * ng * (group / 8);
     const int blocks = static_cast<int>((total + 255) / 256);
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(quantize_rows_kernel, dim3(blocks), dim3(256), 0, stream, W, N, K, group, ng,
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3(blocks), dim3(256), 0, stream, W, N, K, bits, group, ng,
                        static_cast<float>((1 << bits) - 1), codes, scales, zeros);
     return hipGetLastError();
 }
 
 hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const uint16_t* zeros, int N,
-                          int K, int group, void* prepacked, hipStream_t stream) {
-    const PrepackDims d = prepack_dims(N, K, group);
+                          int K, int bits, int group, void* prepacked, hipStream_t stream) {
+    const PrepackDims d = prepack_dims(N, K, group, bits);
     const int ng = (K + group - 1) / group;
     const long n_code = static_cast<long>(d.NF) * d.KT * 64;
     const long n_sz = static_cast<long>(d.NGP) * d.NF * 32;
@@ -153,6 +228,11 @@ hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const u
     if (blocks == 0) return hipSuccess;
     U4* pc = reinterpret_cast<U4*>(prepacked);
     uint32_t* ps = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(prepacked) + d.code_bytes);
+    if (bits == 3) {
+        hipLaunchKernelGGL(prepack3_kernel, dim3(blocks), dim3(256), 0, stream, codes, scales, zeros, N, K,
+                           group, ng, d.NF, d.KT, d.NGP, reinterpret_cast<uint32_t*>(prepacked), ps);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(prepack_kernel, dim3(blocks), dim3(256), 0, stream, codes, scales, zeros, N, K,
                        group, ng, d.NF, d.KT, d.NGP, pc, ps);
     return hipGetLastError();

@@ -61,7 +61,9 @@ def test_size_queries(qt):
     # LLaMA-7B-shaped down projection: 4096 x 11008, group 128
     n = qt.qtale_prepacked_bytes(4096, 11008, 4, 128)
     assert n == 4096 * 11008 // 2 + 4 * 4096 * (11008 // 128)
-    assert qt.qtale_prepacked_bytes(4096, 11008, 3, 128) == 0
+    # 3-bit codes: 12 bytes per lane per k-tile, same scale/zero section
+    assert qt.qtale_prepacked_bytes(4096, 11008, 3, 128) == 4096 * 11008 * 3 // 8 + 4 * 4096 * (11008 // 128)
+    assert qt.qtale_prepacked_bytes(4096, 11008, 2, 128) == 0
     assert qt.qtale_prepacked_bytes(4096, 11008, 4, 100) == 0
     assert qt.qtale_prepacked_bytes(4096, 11006, 4, 128) == 0
     cfg = qt.make_cfg(4096, 32, 32, 128, 11008)
@@ -87,7 +89,7 @@ def test_forward_argument_validation_needs_no_gpu(qt):
     assert call(cfg, T=-1) == -1
     assert call(cfg) == -1                                       # weights without prepacked buffers
     assert call(qt.make_cfg(256, 4, 3, 64, 688, group=32)) == -2  # heads not divisible
-    assert call(qt.make_cfg(256, 4, 4, 64, 688, bits=3, group=32)) == -3
+    assert call(qt.make_cfg(256, 4, 4, 64, 688, bits=2, group=32)) == -3
     assert call(qt.make_cfg(256, 4, 4, 64, 688, group=48)) == -3
     assert call(qt.make_cfg(256, 4, 4, 80, 688, group=32)) == -3
     assert call(qt.make_cfg(250, 4, 4, 64, 688, group=32)) == -2
@@ -102,7 +104,7 @@ def test_forward_argument_validation_needs_no_gpu(qt):
     assert lib.qtale_stack_forward(ctx._h, C.byref(cfg), None, 2, fake, 4, fake, 1, fake, None, None, None, None, None,
                                    fake, 1 << 30, None) == -1
     ql = qt.qtale_qlinear(None, None, None, None, 64, 64)
-    assert lib.qtale_linear_w4a16(C.byref(ql), 32, fake, 4, fake, None) == -1
-    assert lib.qtale_linear_w4a16(C.byref(ql), 48, fake, 4, fake, None) == -3
+    assert lib.qtale_linear_w4a16(C.byref(ql), 4, 32, fake, 4, fake, None) == -1
+    assert lib.qtale_linear_w4a16(C.byref(ql), 4, 48, fake, 4, fake, None) == -3
     assert lib.qtale_quantize(None, 8, 64, 4, 32, fake, fake, fake, None, None) == -1
     assert lib.qtale_quantize(fake, 8, 64, 5, 32, fake, fake, fake, None, None) == -3

@@ -25,23 +25,24 @@ def _w(N, K, seed, std=0.02):
     return torch.randn(N, K, generator=g) * std
 
 
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,K,G", [(256, 256, 32), (256, 688, 32), (688, 256, 32), (100, 136, 64),
                                    (512, 1024, 128), (33, 4096, 128), (4096, 264, 128)])
-def test_quantize_is_bit_exact(qt, N, K, G):
+def test_quantize_is_bit_exact(qt, N, K, G, bits):
     W = _w(N, K, N * 7 + K)
     W[0, : min(K, G)] = 0.0                                     # a constant-zero group
     W[1, : min(K, G)] = W[1, : min(K, G)].abs() + 1e-3          # an all-positive group
-    ql = qt.qtale_quantize(W.cuda(), 4, G)
+    ql = qt.qtale_quantize(W.cuda(), bits, G)
     torch.cuda.synchronize()
-    codes, s, z = orc.quantize_rtn(W.numpy(), 4, G)
-    assert np.array_equal(ql.codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes))
+    codes, s, z = orc.quantize_rtn(W.numpy(), bits, G)
+    assert np.array_equal(ql.codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes, bits))
     assert np.array_equal(ql.scales.cpu().numpy().view(np.uint16), s.view(np.uint16))
     assert np.array_equal(ql.zeros.cpu().numpy().view(np.uint16), z.view(np.uint16))
 
 
 def test_quantize_rejects_bad_parameters(qt):
     W = _w(8, 64, 0).cuda()
-    for bits, group in [(3, 128), (4, 48), (8, 128)]:
+    for bits, group in [(2, 128), (5, 128), (4, 48), (8, 128)]:
         with pytest.raises(qt.QtaleError):
             qt.qtale_quantize(W, bits, group)
     with pytest.raises(qt.QtaleError):
@@ -50,27 +51,57 @@ def test_quantize_rejects_bad_parameters(qt):
 
 @pytest.mark.parametrize("M,N,K,G", [(64, 256, 256, 32), (32, 256, 688, 32), (7, 688, 256, 32), (300, 416, 512, 128),
                                      (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128)])
-def test_linear_w4a16_matches_oracle(qt, M, N, K, G):
+@pytest.mark.parametrize("bits", [4, 3])
+def test_linear_w4a16_matches_oracle(qt, M, N, K, G, bits):
     W = _w(N, K, M + N + K)
     A = torch.randn(M, K, generator=torch.Generator().manual_seed(M)).to(torch.float16)
-    ql = qt.qtale_quantize(W.cuda(), 4, G)
+    ql = qt.qtale_quantize(W.cuda(), bits, G)
     out = qt.qtale_linear_w4a16(ql, A.cuda())
     torch.cuda.synchronize()
-    codes, s, z = orc.quantize_rtn(W.numpy(), 4, G)
+    codes, s, z = orc.quantize_rtn(W.numpy(), bits, G)
+    want = A.to(torch.float64).numpy() @ orc.dequantize(codes, s, z, G).T
+    assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("M,K,N,G", [(256, 256, 96, 32), (64, 64, 512, 64), (512, 512, 40, 128)])
+def test_identity_activations_return_the_dequantized_weights_exactly(qt, M, K, N, G, bits):
+    # A = I: out[m][n] is the single product 1 * W'[n][m], so the kernel's in-register dequantisation
+    # must equal fp16((code - zero) * scale) bit for bit (prefill kernel for M > 64, skinny kernel else)
+    W = _w(N, K, 5 * N + K + bits)
+    ql = qt.qtale_quantize(W.cuda(), bits, G)
+    out = qt.qtale_linear_w4a16(ql, torch.eye(K, dtype=torch.float16).cuda())
+    torch.cuda.synchronize()
+    codes, s, z = orc.quantize_rtn(W.numpy(), bits, G)
+    want = torch.from_numpy(orc.dequantize(codes, s, z, G).T.copy()).to(torch.float16)
+    assert torch.equal(out.cpu(), want)
+
+
+def test_prepack_from_canonical_three_bit_codes(qt):
+    # weights quantized elsewhere (here: by the oracle) and handed over in the canonical 3-bit layout
+    N, K, G = 64, 688, 32
+    W = _w(N, K, 77)
+    codes, s, z = orc.quantize_rtn(W.numpy(), 3, G)
+    words = torch.from_numpy(orc.pack_codes(codes, 3).view(np.int32)).cuda()
+    ql = qt.qtale_prepack(words, torch.from_numpy(s).cuda(), torch.from_numpy(z).cuda(), N, K, 3, G)
+    A = torch.randn(16, K, generator=torch.Generator().manual_seed(4)).to(torch.float16)
+    out = qt.qtale_linear_w4a16(ql, A.cuda())
+    torch.cuda.synchronize()
     want = A.to(torch.float64).numpy() @ orc.dequantize(codes, s, z, G).T
     assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
 
 
 @pytest.mark.parametrize("M,I,K,G", [(64, 688, 256, 32), (200, 352, 512, 128), (5, 64, 128, 64)])
-def test_swiglu_w4a16_matches_oracle(qt, M, I, K, G):
+@pytest.mark.parametrize("bits", [4, 3])
+def test_swiglu_w4a16_matches_oracle(qt, M, I, K, G, bits):
     Wg, Wu = _w(I, K, 1, 0.05), _w(I, K, 2, 0.05)
     A = torch.randn(M, K, generator=torch.Generator().manual_seed(3)).to(torch.float16)
-    qg, qu = qt.qtale_quantize(Wg.cuda(), 4, G), qt.qtale_quantize(Wu.cuda(), 4, G)
+    qg, qu = qt.qtale_quantize(Wg.cuda(), bits, G), qt.qtale_quantize(Wu.cuda(), bits, G)
     out = qt.qtale_swiglu_w4a16(qg, qu, A.cuda())
     torch.cuda.synchronize()
     A64 = A.to(torch.float64).numpy()
-    dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), 4, G), G)
-    du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), 4, G), G)
+    dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), bits, G), G)
+    du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), bits, G), G)
     want = orc.silu(A64 @ dg.T) * (A64 @ du.T)
     assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
 

@@ -81,6 +81,23 @@ def test_layer_group64(qt):
     _check_layer(qt, shape, 150, [150], "threshold", 0.45, seed=3, std=0.08)
 
 
+@pytest.mark.parametrize("mode,val", [("ratio", 0.5), ("threshold", 0.45)])
+def test_three_bit_layer_ragged_k(qt, mode, val):
+    # 3-bit codes (Sec. 4.1), group 32, SwiGLU width 688: the down-proj K is not a multiple of 64
+    shape = si.LayerShape(256, 4, 4, 64, 688, 3, 32, "fp16")
+    _check_layer(qt, shape, 200, [120, 80], mode, val, seed=20, std=0.08, starts=[0, 3])
+
+
+def test_three_bit_layer_gqa_bf16_group128(qt):
+    shape = si.LayerShape(512, 4, 2, 128, 1408, 3, 128, "bf16")
+    _check_layer(qt, shape, 333, [100, 1, 200, 32], "ratio", 0.6, seed=21, std=0.057, starts=[0, 5, 17, 1000])
+
+
+def test_three_bit_decode_step(qt):
+    shape = si.LayerShape(256, 4, 4, 64, 688, 3, 32, "fp16")
+    _cache_case(qt, shape, [1] * 8, [37, 5, 100, 64, 1, 99, 12, 63], [37, 5, 100, 64, 1, 99, 12, 63], 128, 22, 0.6)
+
+
 def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     T = sum(lens)
     B = len(lens)
