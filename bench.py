@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
-def cpu_baseline(shape, seq_len, ratio, n_layers):
-    """Times the CPU oracle (as it stands) on a bounded sample: layer 0, one sequence."""
+def cpu_baseline(shape, n_seq, seq_len, ratio, n_layers, reps=3):
+    """Times the CPU oracle (as it stands) on a bounded sample: layer 0 on the whole batch, `reps` batches."""
     import numpy as np
     import torch
     import synth_inputs as si
@@ -40,15 +40,18 @@ def cpu_baseline(shape, seq_len, ratio, n_layers):
                         f64(t["g1"]), f64(t["g2"]), t["router_w"].numpy(), 0.0)
     cfg = dict(n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
                rms_eps=shape.rms_eps, rope_base=shape.rope_base)
-    x = f64(si.hidden_states(shape, seq_len, 0))
-    offs, pos = si.equal_sequences(1, seq_len)
+    T = n_seq * seq_len
+    xs = [f64(si.hidden_states(shape, T, 0, extra=i)) for i in range(reps)]
+    offs, pos = si.equal_sequences(n_seq, seq_len)
     t0 = time.perf_counter()
-    orc.layer_forward(x, p, cfg, offs.numpy(), pos.numpy(), "ratio", ratio)
-    dt = time.perf_counter() - t0
+    for x in xs:
+        orc.layer_forward(x, p, cfg, offs.numpy(), pos.numpy(), "ratio", ratio)
+    dt = (time.perf_counter() - t0) / reps
     cores = torch.get_num_threads()
-    return {"value": seq_len / (dt * n_layers), "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "oracle layer_forward (fp64 NumPy) on layer 0 and 1 sequence of %d tokens at ratio %.2f: %.2f s; "
-                      "stack rate extrapolated as tokens / (%d layers x layer time)" % (seq_len, ratio, dt, n_layers)}
+    return {"value": T / (dt * n_layers), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "oracle layer_forward (fp64 NumPy) on layer 0 and %d batches of %d x %d tokens at ratio %.2f: "
+                      "%.2f s per batch; stack rate extrapolated as tokens / (%d layers x layer time)"
+                      % (reps, n_seq, seq_len, ratio, dt, n_layers)}
 
 
 def recorded_traffic():
@@ -71,11 +74,11 @@ def recorded_traffic():
     return float(vals["traffic_bytes_per_launch"])
 
 
-def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16):
+def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=4, ratios=(1.0, 0.8, 0.6, 0.4)):
     """Secondary measurement (configs[2]): decode steps of the same stack, batch 64, 2048 cached
     entries per sequence and layer (random fp16 K/V), execution ratio changed at run time."""
     dev = "cuda"
-    shape = si.LayerShape(4096, 32, 32, 128, 11008, 4, 128, "fp16")
+    shape = si.LayerShape(4096, 32, 32, 128, 11008, bits, 128, "fp16")
     cfg = qt.cfg_from_shape(shape)
     fp16_layers = []
     for lw in layers:                                  # same quantized weights, fp16 gains for an fp16 stream
@@ -94,7 +97,7 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16):
     ctx = qt.Context()
     xs = [si.hidden_states(shape, B, 0, slot="x_step", extra=i, device=dev) for i in range(steps)]
     res = {}
-    for r in (1.0, 0.8, 0.6, 0.4):
+    for r in ratios:
         qt.qtale_set_exec_ratio(ctx, r)                 # runtime change: no requantization
         k_exec = int(float(torch.tensor(r, dtype=torch.float32)) * B + 0.5)
 
@@ -118,14 +121,58 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16):
         ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
         lin_ms = ms["qkv_gemm"] + ms["o_gemm"] + ms["gate_up_gemm"] + ms["down_gemm"]
         kv_bytes = k_exec * (ctx_len + steps / 2.0) * 2 * 4096 * 2
-        w_bytes = shape.params_per_layer() // 2 + 4 * (shape.params_per_layer() // 128)
+        w_bytes = shape.params_per_layer() * bits // 8 + 4 * (shape.params_per_layer() // 128)
         res["%.1f" % r] = {"tokens_per_s": B * steps / dt, "ms_per_step": dt * 1e3 / steps,
                            "executed_per_layer": k_exec,
                            "attention_ms": ms["attention"], "attention_GBps": kv_bytes / (ms["attention"] * 1e6),
                            "linears_ms": lin_ms, "weight_stream_GBps": w_bytes / (lin_ms * 1e6)}
-    return {"workload": "configs[2]: same stack in decode, batch %d, %d cached K/V entries per sequence and layer "
-                        "(random fp16), %d steps per ratio, fp16 stream" % (B, ctx_len, steps),
+    return {"workload": "configs[2]: same stack (int%d) in decode, batch %d, %d cached K/V entries per sequence and layer "
+                        "(random fp16), %d steps per ratio, fp16 stream" % (bits, B, ctx_len, steps),
             "hbm_peak_GBps": HBM_PEAK_GBS, "by_exec_ratio": res}
+
+
+def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode):
+    """The 3-bit variant of the same workload (Sec. 4.1 evaluates 4-bit and 3-bit weights): prefill step
+    and gate/up GEMM rate, then two decode ratios."""
+    import dataclasses
+    dev = "cuda"
+    shape = dataclasses.replace(shape4, bits=3)
+    cfg = qt.cfg_from_shape(shape)
+    layers = []
+    for l in range(L):
+        t = si.layer_tensors(shape, l, 0, device=dev)
+        layers.append(qt.quantize_layer(t, 3, shape.group, keep_canonical=False))
+        del t
+    stack = qt.Stack(cfg, layers)
+    T = B * S
+    offs, pos = si.equal_sequences(B, S)
+    offs, pos = offs.to(dev), pos.to(dev)
+    ws = qt.alloc_workspace(cfg, T, B, dev)
+    ctx = qt.Context()
+    qt.qtale_set_exec_ratio(ctx, ratio)
+    k_exec = int(float(torch.tensor(ratio, dtype=torch.float32)) * T + 0.5)
+    xs = [si.hidden_states(shape, T, 0, extra=3000 + i, device=dev) for i in range(4)]
+    qt.qtale_stack_forward(ctx, stack, xs[0], offs, pos, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for x in xs[1:]:
+        qt.qtale_stack_forward(ctx, stack, x, offs, pos, workspace=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / 3
+    xs = [si.hidden_states(shape, T, 0, extra=3000 + i, device=dev) for i in range(2)]
+    qt.qtale_profile_enable(ctx, True)
+    for x in xs:
+        qt.qtale_stack_forward(ctx, stack, x, offs, pos, workspace=ws)
+    prof = qt.qtale_profile_read(ctx)
+    qt.qtale_profile_enable(ctx, False)
+    gu_ms = prof["gate_up_gemm"][0] / prof["gate_up_gemm"][1]
+    out = {"workload": "same stack and batch with 3-bit group-128 codes (0.375 B/weight)",
+           "prefill_tokens_per_s": T / dt, "prefill_ms_per_step": dt * 1e3,
+           "gate_up_gemm_ms": gu_ms, "gate_up_gemm_TFLOPs": 2.0 * k_exec * 2 * shape.inter * shape.hidden / (gu_ms * 1e-3) / 1e12}
+    del xs, ws
+    if not no_decode:
+        out["decode"] = decode_section(qt, si, torch, layers, L, bits=3, ratios=(1.0, 0.4))["by_exec_ratio"]
+    return out
 
 
 def main():
@@ -140,6 +187,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-int3", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates FETCH_SIZE/WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -235,9 +283,12 @@ def main():
             sweep["%.1f" % r] = T * 2 / (time.perf_counter() - t0)
         qt.qtale_set_exec_ratio(ctx, args.ratio)
 
+    del xs, ws
+    int3 = None
+    if not args.no_int3:
+        int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode)
     decode = None
     if not args.no_decode:
-        del xs, ws
         decode = decode_section(qt, si, torch, layers, L)
 
     out = {
@@ -253,9 +304,10 @@ def main():
         "kernel_ms_per_launch": kern_ms,
         "tokens_per_s_vs_exec_ratio": sweep,
         "decode": decode,
+        "int3": int3,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, S, args.ratio, L)
+        out["cpu_baseline"] = cpu_baseline(shape, B, S, args.ratio, L)
     print(json.dumps(out))
 
 
