@@ -14,7 +14,9 @@ What is implemented, and the passage of the paper each part follows:
                                                                     (Sec. 3.4, Eq. 9)
 * active tokens are gathered into a dense matrix before the layer   (App. B.2)
 * weight-only group quantization with groups along the input dimension,
-  4 bit (3 bit also accepted by the quantizer)                     (Sec. 4.1 setup)
+  4 bit and 3 bit                                                   (Sec. 4.1 setup)
+* two-phase grid search for the global theta (coarse 0.05, fine 0.01 on (0, 0.5]),
+  with the average execution ratio as the objective                 (Sec. 3.4)
 
 The paper gives no formula for the quantizer, the router's architecture, or the
 inside of f_l; those follow the readings listed in this repository's design
@@ -30,7 +32,9 @@ closed forms for dequantisation, full-sort check and nesting/monotonicity for
 the selection, ratio 1 == dense layer, ratio 0 == identity, bypassed rows
 bit-identical, agreement with an independent per-token brute-force loop
 (`layer_forward_bruteforce`), torch fp64 library attention/matmul as a third
-opinion, rotary relative-position property, the paper's FLOPs-per-token figure.
+opinion, rotary relative-position property, the paper's FLOPs-per-token figure;
+the theta search against an exhaustive scan of all 50 grid points and a closed-form
+score distribution.
 Numeric values of hidden states: parity unpinned by the paper (it prints no
 activations); pinned only by the self-consistency checks above.
 
@@ -479,6 +483,65 @@ def stack_forward(x, layers, cfg, seq_offsets, positions, mode, control, kvs=Non
             x = round_to(x)
         sel.append(idx)
     return x, sel, inputs
+
+
+# --------------------------------------------------------------------------
+# Threshold calibration (Sec. 3.4: two-phase grid search for the global theta)
+# --------------------------------------------------------------------------
+# The paper searches theta in (0, 0.5] on a small calibration set, first with step 0.05, then with
+# step 0.01 around the best coarse point, and keeps the theta with the best task metric.  Task
+# metrics need the paper's datasets; here the objective is the one its rate loss trains for: the
+# average execution ratio R_avg over layers should hit a target.  theta_n = fp32(n / 100), n = 1..50.
+
+def theta_grid(n):
+    return np.float32(n / 100.0)
+
+
+def two_phase_search(ratio_of_n, target):
+    """ratio_of_n(n) -> R_avg at theta_n.  Coarse pass over n = 5, 10, ..., 50; fine pass over the
+    not-yet-evaluated n within 4 steps of the best coarse point (clipped to 1..50); the answer is the
+    evaluated n with the smallest |R_avg - target|, ties going to the larger theta.
+    Returns (n, R_avg(n), {n: R_avg} of everything evaluated, in evaluation order)."""
+    target = float(target)
+    seen = {}
+
+    def best():
+        return min(seen, key=lambda n: (abs(seen[n] - target), -n))
+
+    for n in range(5, 51, 5):
+        seen[n] = float(ratio_of_n(n))
+    c = best()
+    for n in range(max(1, c - 4), min(50, c + 4) + 1):
+        if n not in seen:
+            seen[n] = float(ratio_of_n(n))
+    b = best()
+    return b, seen[b], seen
+
+
+def calibrate_theta_from_scores(scores, target):
+    """scores: fp32 [L, T] router scores of a calibration batch, taken as fixed.  R_avg(theta) is the
+    fraction of all L*T (layer, token) pairs with p_0 >= theta (Eq. 9)."""
+    z = np.asarray(scores, dtype=np.float32)
+    total = z.size
+
+    def ratio(n):
+        return int(np.count_nonzero(z >= theta_to_logit(theta_grid(n)))) / total
+
+    n, r, seen = two_phase_search(ratio, target)
+    return theta_grid(n), r, seen
+
+
+def calibrate_theta(x, layers, cfg, seq_offsets, positions, target, round_to=None):
+    """Same search with R_avg measured by running the stack in threshold mode on the calibration batch
+    x for every candidate theta (skipping changes the hidden states that later routers see)."""
+    T = np.asarray(x).shape[0]
+
+    def ratio(n):
+        _, sel, _ = stack_forward(x, layers, cfg, seq_offsets, positions, "threshold", theta_grid(n), round_to=round_to)
+        return sum(len(i) for i in sel) / (len(layers) * T)
+
+    n, r, seen = two_phase_search(ratio, target)
+    return theta_grid(n), r, seen
 
 
 def flops_per_token(hidden, n_heads, n_kv_heads, head_dim, inter, n_layers):
