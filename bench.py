@@ -283,6 +283,28 @@ def main():
             sweep["%.1f" % r] = T * 2 / (time.perf_counter() - t0)
         qt.qtale_set_exec_ratio(ctx, args.ratio)
 
+    # threshold mode (Eq. 9 with one global theta, data-dependent count kept on the device): calibrate theta
+    # for the target ratio on one batch with the two-phase grid search, then time steps at that theta
+    threshold = None
+    if not args.no_sweep:
+        xc = batches(1, 4000)[0]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        theta, r_avg, seen = qt.qtale_calibrate_threshold(ctx, stack, xc, offs, pos, args.ratio, workspace=ws)
+        t_cal = time.perf_counter() - t0
+        xs = batches(4, 5000)
+        cnt = torch.zeros(L, dtype=torch.int32, device=dev)
+        qt.qtale_stack_forward(ctx, stack, xs[0], offs, pos, sel_count=cnt, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(xs[1:])
+        torch.cuda.synchronize()
+        dt_thr = (time.perf_counter() - t0) / 3
+        threshold = {"target_ratio": args.ratio, "theta": theta, "calibration_ratio": r_avg,
+                     "candidates_evaluated": len(seen), "calibration_s": t_cal,
+                     "fresh_batch_ratio": float(cnt.sum().item()) / (L * T),
+                     "tokens_per_s": T / dt_thr, "ms_per_step": dt_thr * 1e3}
+        qt.qtale_set_exec_ratio(ctx, args.ratio)
     del xs, ws
     int3 = None
     if not args.no_int3:
@@ -303,6 +325,7 @@ def main():
         "roofline": roofline,
         "kernel_ms_per_launch": kern_ms,
         "tokens_per_s_vs_exec_ratio": sweep,
+        "threshold_mode": threshold,
         "decode": decode,
         "int3": int3,
     }

@@ -167,6 +167,32 @@ int qtale_router_select(qtale_ctx* ctx, int act_dtype, const void* x, int T, int
                         int32_t* cu_exec /*nullable [B+1]: executed tokens before each sequence*/,
                         void* stream);
 
+/* ---- threshold calibration (Sec. 3.4: two-phase grid search for the global theta) --------------------
+ * Candidates theta_n = fp32(n/100), n = 1..50 (the search range (0, 0.5]).  Coarse pass over n = 5, 10,
+ * ..., 50, then the not yet evaluated n within 4 steps of the best coarse point; the result is the evaluated
+ * n whose average execution ratio R_avg is closest to target_ratio (ties: the larger theta).  The paper's
+ * objective is a task metric on calibration data; here it is the execution ratio itself.
+ * Both calls synchronize `stream`, allocate nothing, and on success leave ctx in threshold mode at the theta
+ * found (as qtale_set_threshold would); on failure the control value is unchanged.
+ *   scratch    device, qtale_calibration_scratch_bytes(n_layers) bytes (n_layers = 0 for the score form)
+ *   theta, ratio  host out (nullable): theta found and its R_avg
+ *   table      host out (nullable) [50]: R_avg of every evaluated candidate at index n-1, NaN elsewhere */
+#define QTALE_THETA_GRID 50
+size_t qtale_calibration_scratch_bytes(int n_layers);
+/* Scores taken as fixed: scores is a device array of n fp32 router scores (e.g. [L][T] written by a forward
+ * call); R_avg(theta) = fraction of them with sigmoid(z) >= theta, decided as in qtale_set_threshold. */
+int qtale_calibrate_threshold_from_scores(qtale_ctx* ctx, const float* scores, int64_t n, float target_ratio,
+                                          void* scratch, float* theta, float* ratio, float* table, void* stream);
+/* R_avg measured: for every candidate the stack runs in threshold mode on the calibration batch (skipping
+ * changes the hidden states later routers see) and R_avg = executed (layer, token) pairs / (n_layers * T).
+ * x_calib [T][hidden] act dtype is only read; x_work (same size) is overwritten.  No K/V cache is used.
+ * Other arguments as in qtale_stack_forward. */
+int qtale_calibrate_threshold(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* layers,
+                              int n_layers, const void* x_calib, void* x_work, int T,
+                              const int32_t* seq_offsets, int B, const int32_t* positions, float target_ratio,
+                              void* scratch, void* workspace, size_t workspace_bytes,
+                              float* theta, float* ratio, float* table, void* stream);
+
 /* out[M][N] (fp16) = A[M][K] (fp16) x dequant(W)^T for one quantized linear (matrix-core GEMM on 4-bit or
  * 3-bit codes, `bits`/`group` as given to qtale_quantize for this matrix). */
 int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* A, int M, void* out, void* stream);

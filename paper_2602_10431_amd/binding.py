@@ -22,7 +22,9 @@ ERRORS = {-1: "INVALID_ARG", -2: "SHAPE", -3: "UNSUPPORTED", -4: "WORKSPACE_TOO_
 EXPORTS = ["qtale_strerror", "qtale_create", "qtale_destroy", "qtale_set_exec_ratio", "qtale_set_threshold",
            "qtale_get_control", "qtale_prepacked_bytes", "qtale_quantize", "qtale_prepack",
            "qtale_workspace_bytes", "qtale_layer_forward", "qtale_stack_forward", "qtale_router_select",
-           "qtale_linear_w4a16", "qtale_swiglu_w4a16", "qtale_profile_enable", "qtale_profile_read"]
+           "qtale_linear_w4a16", "qtale_swiglu_w4a16", "qtale_profile_enable", "qtale_profile_read",
+           "qtale_calibration_scratch_bytes", "qtale_calibrate_threshold_from_scores", "qtale_calibrate_threshold"]
+QTALE_THETA_GRID = 50
 
 
 class QtaleError(RuntimeError):
@@ -84,10 +86,17 @@ def load_library():
     lib.qtale_router_select.argtypes = [vp, i, vp, i, i, vp, f, vp, i, vp, vp, vp, vp, vp]
     lib.qtale_linear_w4a16.argtypes = [C.POINTER(qtale_qlinear), i, i, vp, i, vp, vp]
     lib.qtale_swiglu_w4a16.argtypes = [C.POINTER(qtale_qlinear), C.POINTER(qtale_qlinear), i, i, vp, i, vp, vp]
+    fp = C.POINTER(C.c_float)
+    lib.qtale_calibration_scratch_bytes.argtypes = [i]
+    lib.qtale_calibration_scratch_bytes.restype = C.c_size_t
+    lib.qtale_calibrate_threshold_from_scores.argtypes = [vp, vp, C.c_int64, C.c_float, vp, fp, fp, fp, vp]
+    lib.qtale_calibrate_threshold.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, vp,
+                                              i, vp, i, vp, C.c_float, vp, vp, C.c_size_t, fp, fp, fp, vp]
     lib.qtale_profile_enable.argtypes = [vp, i]
     lib.qtale_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     for name in EXPORTS:
-        if name not in ("qtale_strerror", "qtale_prepacked_bytes", "qtale_workspace_bytes"):
+        if name not in ("qtale_strerror", "qtale_prepacked_bytes", "qtale_workspace_bytes",
+                        "qtale_calibration_scratch_bytes"):
             getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -264,6 +273,42 @@ def qtale_stack_forward(ctx, stack, x, seq_offsets, positions, sel_idx=None, sel
         ctx._h, C.byref(stack.cfg), stack._w, stack.n, _ptr(x), T, _ptr(seq_offsets), B, _ptr(positions),
         stack._kv, _ptr(sel_idx), _ptr(sel_count), _ptr(scores), _ptr(dbg_hidden), _ptr(workspace),
         workspace.numel(), _stream()), "qtale_stack_forward")
+
+
+def _calibration_result(theta, ratio, table):
+    seen = {n + 1: float(table[n]) for n in range(QTALE_THETA_GRID) if table[n] == table[n]}   # NaN = not evaluated
+    return float(theta.value), float(ratio.value), seen
+
+
+def qtale_calibrate_threshold_from_scores(ctx, scores, target_ratio):
+    """scores: fp32 CUDA tensor (any shape).  Returns (theta, R_avg, {n: R_avg of theta = n/100}); ctx is left
+    in threshold mode at theta."""
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+    lib = load_library()
+    scratch = torch.empty(lib.qtale_calibration_scratch_bytes(0), dtype=torch.uint8, device=scores.device)
+    theta, ratio, table = C.c_float(), C.c_float(), (C.c_float * QTALE_THETA_GRID)()
+    _check(lib.qtale_calibrate_threshold_from_scores(ctx._h, _ptr(scores), scores.numel(), float(target_ratio),
+                                                     _ptr(scratch), C.byref(theta), C.byref(ratio), table, _stream()),
+           "qtale_calibrate_threshold_from_scores")
+    return _calibration_result(theta, ratio, table)
+
+
+def qtale_calibrate_threshold(ctx, stack, x_calib, seq_offsets, positions, target_ratio, workspace=None):
+    """Runs the stack in threshold mode on the calibration batch for every candidate theta.  x_calib is not
+    modified.  Returns (theta, R_avg, {n: R_avg}); ctx is left in threshold mode at theta."""
+    T = x_calib.shape[0]
+    B = seq_offsets.numel() - 1
+    lib = load_library()
+    if workspace is None:
+        workspace = alloc_workspace(stack.cfg, T, B, x_calib.device)
+    scratch = torch.empty(lib.qtale_calibration_scratch_bytes(stack.n), dtype=torch.uint8, device=x_calib.device)
+    x_work = torch.empty_like(x_calib)
+    theta, ratio, table = C.c_float(), C.c_float(), (C.c_float * QTALE_THETA_GRID)()
+    _check(lib.qtale_calibrate_threshold(ctx._h, C.byref(stack.cfg), stack._w, stack.n, _ptr(x_calib), _ptr(x_work), T,
+                                         _ptr(seq_offsets), B, _ptr(positions), float(target_ratio), _ptr(scratch),
+                                         _ptr(workspace), workspace.numel(), C.byref(theta), C.byref(ratio), table,
+                                         _stream()), "qtale_calibrate_threshold")
+    return _calibration_result(theta, ratio, table)
 
 
 def qtale_router_select(ctx, x, router_w, router_b=0.0, seq_offsets=None):

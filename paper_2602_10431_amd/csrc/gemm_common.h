@@ -9,7 +9,7 @@ namespace qtale {
 struct GemmDev {
     const half_t* A;
     const int32_t* count;
-    int M_max, K, KT, gshift;
+    int M_max, rows_exact, K, KT, gshift;
     const void* codes[3];
     const uint32_t* sz[3];
     int N[3], NF[3], npad[3], colbase[3];

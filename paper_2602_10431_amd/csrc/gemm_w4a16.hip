@@ -17,11 +17,13 @@
 //   * Epilogues fuse what follows the linear: fp16 store (q|k|v), residual add from the gathered rows
 //     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
 //     The accumulators are transposed through LDS so that every global access is row-contiguous.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 namespace qtale {
 
-template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED>
+template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC, bool RAGGED, bool PERSIST>
 __global__ void __launch_bounds__(WM * WN * 64, OCC)
 gemm_w4a16_kernel(GemmDev p) {
     using WB = WBits<BITS>;
@@ -37,11 +39,16 @@ gemm_w4a16_kernel(GemmDev p) {
     __shared__ __attribute__((aligned(16))) char smem[kABytes > kCBytes ? kABytes : kCBytes];
     half_t (*As)[BM * kLdsStride] = reinterpret_cast<half_t (*)[BM * kLdsStride]>(smem);
 
+    // Two launch forms.  PERSIST = false: one workgroup per tile, the host knows the row count (ratio mode).
+    // PERSIST = true: the grid is sized for the chip, not for the worst-case row count, and every workgroup
+    // walks the tiles that actually hold executed rows (in threshold mode M is a device-side count that may
+    // be far below the host bound; one workgroup per worst-case tile made the dispatcher, not the matrix
+    // cores, the bottleneck: +31 % at half the rows).  Consecutive tiles run down the rows of one column
+    // panel, and with a grid that is a multiple of 8 a workgroup stays on the row tiles congruent to its
+    // XCD, so an XCD's L2 keeps seeing the same few A panels.
     const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
-    const int tile_m = blockIdx.x % p.tiles_m;
-    const int tile_n = blockIdx.x / p.tiles_m;
-    const int m0 = tile_m * BM;
-    if (m0 >= M) return;
+    const int live_m = (M + BM - 1) / BM;
+    const int n_tiles = live_m * p.tiles_n;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -51,6 +58,11 @@ gemm_w4a16_kernel(GemmDev p) {
     const int l32 = lane & 31;
     const int lhi = lane >> 5;
     const uint32_t magic = dequant_magic();
+
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int tile_m = tile % live_m;
+    const int tile_n = tile / live_m;
+    const int m0 = tile_m * BM;
 
     // ---- which weight fragments this wave owns (all wave-uniform -> scalar base addresses) ------
     const char* bbase[FN];
@@ -298,6 +310,22 @@ gemm_w4a16_kernel(GemmDev p) {
             }
         }
     }
+    if (!PERSIST) break;   // one tile per workgroup: straight-line code, registers of the main loop die here
+    __syncthreads();       // the next tile's A staging overlays the epilogue slabs
+    }  // tile loop
+}
+
+// Workgroups the chip holds at once at `occ` per CU (queried once per device).
+static int resident_workgroups(int occ) {
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256 * occ;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev] * occ;
 }
 
 template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC>
@@ -306,12 +334,22 @@ static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     constexpr int BNF = WN * FN;
     d.tiles_m = (d.M_max + BM - 1) / BM;
     d.tiles_n = (d.vf_total + BNF - 1) / BNF;
-    const int blocks = d.tiles_m * d.tiles_n;
+    // exact row count: one workgroup per tile, scheduled by the hardware as slots free up; a host bound that
+    // may be far above the device-side count: as many workgroups as fit on the chip, each walking its tiles
+    const int blocks = d.rows_exact ? d.tiles_m * d.tiles_n : std::min(d.tiles_m * d.tiles_n, resident_workgroups(OCC));
     if (blocks == 0) return hipSuccess;
-    if (d.K % 64 != 0)
-        hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, true>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
-    else
-        hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, false>), dim3(blocks), dim3(WM * WN * 64), 0, stream, d);
+    const dim3 grid(blocks), block(WM * WN * 64);
+    if (d.rows_exact) {
+        if (d.K % 64 != 0)
+            hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, true, false>), grid, block, 0, stream, d);
+        else
+            hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, false, false>), grid, block, 0, stream, d);
+    } else {
+        if (d.K % 64 != 0)
+            hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, true, true>), grid, block, 0, stream, d);
+        else
+            hipLaunchKernelGGL((gemm_w4a16_kernel<BITS, WM, WN, FM, FN, GPT, EPI, OCC, false, true>), grid, block, 0, stream, d);
+    }
     return hipGetLastError();
 }
 
@@ -336,6 +374,7 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     d.A = reinterpret_cast<const half_t*>(a.A);
     d.count = a.count;
     d.M_max = a.M_max;
+    d.rows_exact = a.rows_exact;
     d.K = a.K;
     d.KT = (a.K + 63) / 64;
     d.gshift = a.group == 32 ? 5 : a.group == 64 ? 6 : 7;

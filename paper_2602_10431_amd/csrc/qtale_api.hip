@@ -6,6 +6,7 @@
 // In ratio mode the executed count k is known on the host, so every launch shape is static and the
 // stack runs without any device->host synchronisation; in threshold mode grids are sized for all T
 // tokens and the kernels read the device-side count.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -204,7 +205,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 3);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 3;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 3;
         g.w[0] = {w->q.prepacked, w->q.N, w->q.K};
         g.w[1] = {w->k.prepacked, w->k.N, w->k.K};
         g.w[2] = {w->v.prepacked, w->v.N, w->v.K};
@@ -232,7 +233,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 6);
         GemmArgs g{};
-        g.A = ws.attn; g.count = count; g.M_max = M_max; g.K = nh * d; g.group = c->group; g.bits = c->bits; g.n_w = 1;
+        g.A = ws.attn; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = nh * d; g.group = c->group; g.bits = c->bits; g.n_w = 1;
         g.w[0] = {w->o.prepacked, w->o.N, w->o.K};
         g.epilogue = EPI_RESID_F32; g.out = ws.h; g.ldo = H; g.resid = x; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));
@@ -244,7 +245,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 8);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 2;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 2;
         g.w[0] = {w->gate.prepacked, w->gate.N, w->gate.K};
         g.w[1] = {w->up.prepacked, w->up.N, w->up.K};
         g.epilogue = EPI_SWIGLU_F16; g.out = ws.act; g.ldo = I;
@@ -253,7 +254,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 9);
         GemmArgs g{};
-        g.A = ws.act; g.count = count; g.M_max = M_max; g.K = I; g.group = c->group; g.bits = c->bits; g.n_w = 1;
+        g.A = ws.act; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = I; g.group = c->group; g.bits = c->bits; g.n_w = 1;
         g.w[0] = {w->down.prepacked, w->down.N, w->down.K};
         g.epilogue = EPI_RESID_SCATTER; g.out = x; g.ldo = H; g.resid = ws.h; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));
@@ -278,6 +279,49 @@ int check_forward_args(qtale_ctx* ctx, const qtale_layer_cfg* cfg, void* x, int 
 int check_kv(const qtale_kv* kv) {
     if (!kv) return QTALE_OK;
     if (!kv->k_cache || !kv->v_cache || !kv->kv_len || kv->cap <= 0) return QTALE_ERR_INVALID_ARG;
+    return QTALE_OK;
+}
+
+}  // namespace
+
+// ---- threshold calibration helpers (Sec. 3.4) --------------------------------------------------------------
+namespace {
+
+float theta_grid(int n) { return static_cast<float>(n / 100.0); }
+
+// Coarse pass n = 5, 10, ..., 50, then the unevaluated n within 4 steps of the best coarse point; the answer is
+// the evaluated n with the smallest |R - target|, the larger theta on ties.  table[n] (n = 1..50) keeps every
+// evaluated ratio, NaN elsewhere.  eval(n, &ratio) returns a QTALE status.
+template <class Eval>
+int two_phase_search(Eval&& eval, double target, double* table, int* best_n) {
+    for (int n = 0; n <= kThetaGrid; ++n) table[n] = std::nan("");
+    auto pick = [&]() {
+        int b = -1;
+        double bd = INFINITY;
+        for (int n = 1; n <= kThetaGrid; ++n) {
+            if (std::isnan(table[n])) continue;
+            const double d = std::fabs(table[n] - target);
+            if (d <= bd) { b = n; bd = d; }
+        }
+        return b;
+    };
+    int e;
+    for (int n = 5; n <= kThetaGrid; n += 5)
+        if ((e = eval(n, &table[n]))) return e;
+    const int c = pick();
+    for (int n = std::max(1, c - 4); n <= std::min(kThetaGrid, c + 4); ++n)
+        if (std::isnan(table[n]) && (e = eval(n, &table[n]))) return e;
+    *best_n = pick();
+    return QTALE_OK;
+}
+
+int finish_calibration(qtale_ctx* ctx, const double* table, int best, float* theta, float* ratio, float* table_out) {
+    ctx->mode = QTALE_MODE_THRESHOLD;
+    ctx->value = theta_grid(best);
+    if (theta) *theta = ctx->value;
+    if (ratio) *ratio = static_cast<float>(table[best]);
+    if (table_out)
+        for (int n = 1; n <= kThetaGrid; ++n) table_out[n - 1] = static_cast<float>(table[n]);
     return QTALE_OK;
 }
 
@@ -433,6 +477,88 @@ int qtale_router_select(qtale_ctx* ctx, int act_dtype, const void* x, int T, int
     return QTALE_OK;
 }
 
+// ---- threshold calibration (Sec. 3.4) --------------------------------------------------------------------
+size_t qtale_calibration_scratch_bytes(int n_layers) {
+    if (n_layers < 0) return 0;
+    return 1024 + static_cast<size_t>(n_layers) * 4;
+}
+
+int qtale_calibrate_threshold_from_scores(qtale_ctx* ctx, const float* scores, int64_t n, float target_ratio,
+                                          void* scratch, float* theta, float* ratio, float* table_out, void* stream) {
+    if (!ctx || n < 0 || !(target_ratio >= 0.0f && target_ratio <= 1.0f)) return QTALE_ERR_INVALID_ARG;
+    if (n == 0 || !scores || !scratch) return QTALE_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned long long* bins = reinterpret_cast<unsigned long long*>(scratch);
+    float* zthr_dev = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + 512);
+    float zthr[kThetaGrid];
+    for (int j = 0; j < kThetaGrid; ++j) zthr[j] = theta_to_logit(theta_grid(j + 1));
+    HIP_TRY(hipMemcpyAsync(zthr_dev, zthr, sizeof(zthr), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));                  // zthr is a stack array: the copy must have left it
+    HIP_TRY(launch_threshold_bins(scores, static_cast<long>(n), zthr_dev, bins, s));
+    unsigned long long host_bins[kThetaGrid + 1];
+    HIP_TRY(hipMemcpyAsync(host_bins, bins, sizeof(host_bins), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    // a score in bin b reaches thresholds 1..b: count(theta_j) = sum of bins j..50
+    unsigned long long reach[kThetaGrid + 2];
+    reach[kThetaGrid + 1] = 0;
+    for (int j = kThetaGrid; j >= 1; --j) reach[j] = reach[j + 1] + host_bins[j];
+    double table[kThetaGrid + 1];
+    int best = -1;
+    const int e = two_phase_search(
+        [&](int j, double* r) {
+            *r = static_cast<double>(reach[j]) / static_cast<double>(n);
+            return QTALE_OK;
+        },
+        static_cast<double>(target_ratio), table, &best);
+    if (e) return e;
+    return finish_calibration(ctx, table, best, theta, ratio, table_out);
+}
+
+int qtale_calibrate_threshold(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* layers,
+                              int n_layers, const void* x_calib, void* x_work, int T, const int32_t* seq_offsets,
+                              int B, const int32_t* positions, float target_ratio, void* scratch, void* workspace,
+                              size_t workspace_bytes, float* theta, float* ratio, float* table_out, void* stream) {
+    if (!(target_ratio >= 0.0f && target_ratio <= 1.0f)) return QTALE_ERR_INVALID_ARG;
+    int e = check_forward_args(ctx, cfg, x_work, T, seq_offsets, B, positions, workspace, workspace_bytes);
+    if (e) return e;
+    if (n_layers <= 0 || !layers || T <= 0 || !x_calib || !scratch) return QTALE_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if ((e = check_weights(cfg, &layers[l]))) return e;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    int32_t* counts_dev = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(scratch) + 1024);
+    std::vector<int32_t> counts(static_cast<size_t>(n_layers));
+    const size_t x_bytes = static_cast<size_t>(T) * cfg->hidden * 2;
+    const int saved_mode = ctx->mode;
+    const float saved_value = ctx->value;
+    const bool saved_prof = ctx->profiling;
+    ctx->profiling = false;
+    double table[kThetaGrid + 1];
+    int best = -1;
+    e = two_phase_search(
+        [&](int n, double* r) {
+            ctx->mode = QTALE_MODE_THRESHOLD;
+            ctx->value = theta_grid(n);
+            if (hipMemcpyAsync(x_work, x_calib, x_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return (int)QTALE_ERR_HIP;
+            const int st = qtale_stack_forward(ctx, cfg, layers, n_layers, x_work, T, seq_offsets, B, positions, nullptr,
+                                               nullptr, counts_dev, nullptr, nullptr, workspace, workspace_bytes, stream);
+            if (st) return st;
+            if (hipMemcpyAsync(counts.data(), counts_dev, counts.size() * 4, hipMemcpyDeviceToHost, s) != hipSuccess) return (int)QTALE_ERR_HIP;
+            if (hipStreamSynchronize(s) != hipSuccess) return (int)QTALE_ERR_HIP;
+            long total = 0;
+            for (int32_t c : counts) total += c;
+            *r = static_cast<double>(total) / (static_cast<double>(n_layers) * static_cast<double>(T));
+            return (int)QTALE_OK;
+        },
+        static_cast<double>(target_ratio), table, &best);
+    ctx->profiling = saved_prof;
+    if (e) {
+        ctx->mode = saved_mode;
+        ctx->value = saved_value;
+        return e;
+    }
+    return finish_calibration(ctx, table, best, theta, ratio, table_out);
+}
+
 int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* A, int M, void* out, void* stream) {
     if (!w || M < 0) return QTALE_ERR_INVALID_ARG;
     int e = check_quant_params(w->N, w->K, bits, group);
@@ -441,7 +567,7 @@ int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* 
     if (M == 0) return QTALE_OK;
     if (!w->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
-    g.A = A; g.M_max = M; g.K = w->K; g.group = group; g.bits = bits; g.n_w = 1;
+    g.A = A; g.M_max = M; g.rows_exact = 1; g.K = w->K; g.group = group; g.bits = bits; g.n_w = 1;
     g.w[0] = {w->prepacked, w->N, w->K};
     g.epilogue = EPI_STORE_F16; g.out = out; g.ldo = w->N;
     HIP_TRY(launch_gemm_w4a16(g, reinterpret_cast<hipStream_t>(stream)));
@@ -457,7 +583,7 @@ int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int b
     if (M == 0) return QTALE_OK;
     if (!gate->prepacked || !up->prepacked || !A || !out) return QTALE_ERR_INVALID_ARG;
     GemmArgs g{};
-    g.A = A; g.M_max = M; g.K = gate->K; g.group = group; g.bits = bits; g.n_w = 2;
+    g.A = A; g.M_max = M; g.rows_exact = 1; g.K = gate->K; g.group = group; g.bits = bits; g.n_w = 2;
     g.w[0] = {gate->prepacked, gate->N, gate->K};
     g.w[1] = {up->prepacked, up->N, up->K};
     g.epilogue = EPI_SWIGLU_F16; g.out = out; g.ldo = gate->N;

@@ -40,6 +40,12 @@ struct SelectArgs {
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 
+// Threshold calibration: bins[b] (kThetaGrid + 1 counters, cleared here) = number of scores that reach exactly
+// b of the kThetaGrid ascending thresholds zthr_dev (device array).
+constexpr int kThetaGrid = 50;
+hipError_t launch_threshold_bins(const float* scores, long n, const float* zthr_dev, unsigned long long* bins,
+                                 hipStream_t stream);
+
 // ---- row operations ---------------------------------------------------------------------------
 // n1[i] = fp16(rmsnorm(x[idx[i]]) * gain) for i < *count
 hipError_t launch_gather_rmsnorm(const void* x, int bf16, int H, const int32_t* idx, const int32_t* count,
@@ -73,7 +79,8 @@ struct GemmWeights {
 struct GemmArgs {
     const void* A;             // [M][K] fp16
     const int32_t* count;      // device row count (nullable: use M_max)
-    int M_max;                 // host upper bound of rows (grid size)
+    int M_max;                 // host upper bound of rows
+    int rows_exact;            // nonzero: the row count equals M_max (ratio mode), no tile will be empty
     int K;
     int group;
     int bits;                  // 4 or 3

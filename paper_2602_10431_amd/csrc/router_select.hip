@@ -213,4 +213,42 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// Threshold calibration (Sec. 3.4): for fixed scores, how many (layer, token) pairs would execute at each of
+// the grid thresholds.  zthr[j] ascends with j; a score falls into bin b = number of thresholds it reaches,
+// so the count at threshold j is the sum of bins j+1 .. NTHR.  Integer atomics only: deterministic.
+__global__ void __launch_bounds__(256)
+threshold_bins_kernel(const float* __restrict__ scores, long n, const float* __restrict__ zthr,
+                      unsigned long long* __restrict__ bins) {
+    __shared__ unsigned int local[kThetaGrid + 1];
+    __shared__ float zt[kThetaGrid];
+    for (int i = threadIdx.x; i <= kThetaGrid; i += blockDim.x) local[i] = 0u;
+    for (int i = threadIdx.x; i < kThetaGrid; i += blockDim.x) zt[i] = zthr[i];
+    __syncthreads();
+    const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float z = scores[i];
+        int lo = 0, hi = kThetaGrid;                 // first j with !(z >= zthr[j]); NaN reaches none
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (z >= zt[mid]) lo = mid + 1; else hi = mid;
+        }
+        atomicAdd(&local[lo], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i <= kThetaGrid; i += blockDim.x)
+        if (local[i]) atomicAdd(&bins[i], static_cast<unsigned long long>(local[i]));
+}
+
+hipError_t launch_threshold_bins(const float* scores, long n, const float* zthr_dev, unsigned long long* bins,
+                                 hipStream_t stream) {
+    hipError_t e = hipMemsetAsync(bins, 0, (kThetaGrid + 1) * sizeof(unsigned long long), stream);
+    if (e != hipSuccess) return e;
+    if (n == 0) return hipSuccess;
+    long blocks = (n + 256L * 8 - 1) / (256L * 8);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(threshold_bins_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, scores, n,
+                       zthr_dev, bins);
+    return hipGetLastError();
+}
+
 }  // namespace qtale

@@ -108,3 +108,25 @@ def test_forward_argument_validation_needs_no_gpu(qt):
     assert lib.qtale_linear_w4a16(C.byref(ql), 4, 48, fake, 4, fake, None) == -3
     assert lib.qtale_quantize(None, 8, 64, 4, 32, fake, fake, fake, None, None) == -1
     assert lib.qtale_quantize(fake, 8, 64, 5, 32, fake, fake, fake, None, None) == -3
+
+
+def test_calibration_argument_validation_needs_no_gpu(qt):
+    lib = qt.load_library()
+    ctx = qt.Context()
+    fake = C.c_void_p(256)
+    assert lib.qtale_calibration_scratch_bytes(32) >= 1024 + 32 * 4
+    assert lib.qtale_calibration_scratch_bytes(-1) == 0
+    nan = float("nan")
+    assert lib.qtale_calibrate_threshold_from_scores(ctx._h, fake, 100, nan, fake, None, None, None, None) == -1
+    assert lib.qtale_calibrate_threshold_from_scores(ctx._h, fake, 100, 1.5, fake, None, None, None, None) == -1
+    assert lib.qtale_calibrate_threshold_from_scores(ctx._h, None, 100, 0.5, fake, None, None, None, None) == -1
+    assert lib.qtale_calibrate_threshold_from_scores(ctx._h, fake, 0, 0.5, fake, None, None, None, None) == -1
+    assert lib.qtale_calibrate_threshold_from_scores(None, fake, 100, 0.5, fake, None, None, None, None) == -1
+    cfg = qt.make_cfg(256, 4, 4, 64, 688, group=32)
+    assert lib.qtale_calibrate_threshold(ctx._h, C.byref(cfg), None, 2, fake, fake, 4, fake, 1, fake, 0.5, fake, fake,
+                                         1 << 30, None, None, None, None) == -1
+    assert lib.qtale_calibrate_threshold(ctx._h, C.byref(cfg), None, 2, fake, fake, 4, fake, 1, fake, -0.1, fake, fake,
+                                         1 << 30, None, None, None, None) == -1
+    mode, value = qt.qtale_get_control(ctx)                      # failed calls leave the control untouched
+    assert mode == qt.QTALE_MODE_RATIO and value == 1.0
+
