@@ -113,8 +113,30 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=
             torch.cuda.synchronize()
             return time.perf_counter() - t0
 
+        def run_graph():
+            # the same steps replayed from one HIP graph: x and positions are rewritten in place
+            x_buf = torch.empty_like(xs[0])
+            pos_buf = torch.empty(B, dtype=torch.int32, device=dev)
+            for kv in kvs:
+                kv.kv_len.fill_(ctx_len)
+            graph = qt.StackGraph(ctx, stack, x_buf, offs, pos_buf, workspace=ws)
+            best = None
+            for _ in range(2):
+                for kv in kvs:
+                    kv.kv_len.fill_(ctx_len)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(steps):
+                    x_buf.copy_(xs[i])
+                    pos_buf.fill_(ctx_len + i)
+                    graph.launch()
+                torch.cuda.synchronize()
+                best = time.perf_counter() - t0
+            return best
+
         run(False)
         dt = run(False)
+        dt_graph = run_graph()
         run(True)
         prof = qt.qtale_profile_read(ctx)
         qt.qtale_profile_enable(ctx, False)
@@ -123,6 +145,7 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=
         kv_bytes = k_exec * (ctx_len + steps / 2.0) * 2 * 4096 * 2
         w_bytes = shape.params_per_layer() * bits // 8 + 4 * (shape.params_per_layer() // 128)
         res["%.1f" % r] = {"tokens_per_s": B * steps / dt, "ms_per_step": dt * 1e3 / steps,
+                           "hip_graph_ms_per_step": dt_graph * 1e3 / steps,
                            "executed_per_layer": k_exec,
                            "attention_ms": ms["attention"], "attention_GBps": kv_bytes / (ms["attention"] * 1e6),
                            "linears_ms": lin_ms, "weight_stream_GBps": w_bytes / (lin_ms * 1e6)}
@@ -312,6 +335,9 @@ def main():
     decode = None
     if not args.no_decode:
         decode = decode_section(qt, si, torch, layers, L)
+        small = decode_section(qt, si, torch, layers, L, B=8, ratios=(1.0, 0.5))
+        decode["batch_8"] = {r: {k: v[k] for k in ("tokens_per_s", "ms_per_step", "hip_graph_ms_per_step", "executed_per_layer")}
+                             for r, v in small["by_exec_ratio"].items()}
 
     out = {
         "metric": "tokens/s of quantized token-adaptive layer stack vs exec ratio; % HBM/MFMA peak",

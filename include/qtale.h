@@ -201,6 +201,25 @@ int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* 
 int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int bits, int group,
                        const void* A, int M, void* out, void* stream);
 
+/* ---- HIP graph of one stack forward (launch-overhead removal, App. B.2 future work) -------------------
+ * qtale_graph_capture_stack records the kernels of ONE qtale_stack_forward call with exactly these
+ * arguments (no dbg_hidden) into a HIP graph and instantiates it; nothing executes during capture.
+ * Every pointer and the control value of ctx at capture time are baked in (in ratio mode the launch shapes
+ * depend on the ratio): to step a decode loop the caller rewrites x, positions and the caches' contents in
+ * place between launches; per-sequence cache lengths advance on the device as in the eager call.  After
+ * qtale_set_exec_ratio / qtale_set_threshold a new graph must be captured.  Fails with
+ * QTALE_ERR_INVALID_ARG while per-kernel profiling is enabled.
+ * qtale_graph_launch enqueues one replay on `stream`; replays of one graph must not overlap. */
+typedef struct qtale_graph qtale_graph;
+int qtale_graph_capture_stack(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* layers,
+                              int n_layers, void* x, int T, const int32_t* seq_offsets, int B,
+                              const int32_t* positions, const qtale_kv* kv_per_layer /*nullable*/,
+                              int32_t* sel_idx /*nullable*/, int32_t* sel_count /*nullable*/,
+                              float* scores /*nullable*/, void* workspace, size_t workspace_bytes,
+                              qtale_graph** graph /*host out*/);
+int qtale_graph_launch(qtale_graph* graph, void* stream);
+void qtale_graph_destroy(qtale_graph* graph);
+
 /* Per-kernel timing with HIP events recorded on the forward call's stream.  While enabled, every
  * layer/stack forward brackets its kernels with events; qtale_profile_read waits for them and
  * returns, per kernel class, accumulated milliseconds and launch counts since the last read.

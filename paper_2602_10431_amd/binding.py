@@ -23,7 +23,8 @@ EXPORTS = ["qtale_strerror", "qtale_create", "qtale_destroy", "qtale_set_exec_ra
            "qtale_get_control", "qtale_prepacked_bytes", "qtale_quantize", "qtale_prepack",
            "qtale_workspace_bytes", "qtale_layer_forward", "qtale_stack_forward", "qtale_router_select",
            "qtale_linear_w4a16", "qtale_swiglu_w4a16", "qtale_profile_enable", "qtale_profile_read",
-           "qtale_calibration_scratch_bytes", "qtale_calibrate_threshold_from_scores", "qtale_calibrate_threshold"]
+           "qtale_calibration_scratch_bytes", "qtale_calibrate_threshold_from_scores", "qtale_calibrate_threshold",
+           "qtale_graph_capture_stack", "qtale_graph_launch", "qtale_graph_destroy"]
 QTALE_THETA_GRID = 50
 
 
@@ -92,11 +93,16 @@ def load_library():
     lib.qtale_calibrate_threshold_from_scores.argtypes = [vp, vp, C.c_int64, C.c_float, vp, fp, fp, fp, vp]
     lib.qtale_calibrate_threshold.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, vp,
                                               i, vp, i, vp, C.c_float, vp, vp, C.c_size_t, fp, fp, fp, vp]
+    lib.qtale_graph_capture_stack.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, i, vp,
+                                              i, vp, C.POINTER(qtale_kv), vp, vp, vp, vp, C.c_size_t, C.POINTER(vp)]
+    lib.qtale_graph_launch.argtypes = [vp, vp]
+    lib.qtale_graph_destroy.argtypes = [vp]
+    lib.qtale_graph_destroy.restype = None
     lib.qtale_profile_enable.argtypes = [vp, i]
     lib.qtale_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     for name in EXPORTS:
         if name not in ("qtale_strerror", "qtale_prepacked_bytes", "qtale_workspace_bytes",
-                        "qtale_calibration_scratch_bytes"):
+                        "qtale_calibration_scratch_bytes", "qtale_graph_destroy"):
             getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -309,6 +315,31 @@ def qtale_calibrate_threshold(ctx, stack, x_calib, seq_offsets, positions, targe
                                          _ptr(workspace), workspace.numel(), C.byref(theta), C.byref(ratio), table,
                                          _stream()), "qtale_calibrate_threshold")
     return _calibration_result(theta, ratio, table)
+
+
+class StackGraph:
+    """HIP graph of one qtale_stack_forward call; holds references to every baked-in tensor."""
+
+    def __init__(self, ctx, stack, x, seq_offsets, positions, sel_idx=None, sel_count=None, scores=None, workspace=None):
+        T = x.shape[0]
+        B = seq_offsets.numel() - 1
+        if workspace is None:
+            workspace = alloc_workspace(stack.cfg, T, B, x.device)
+        self._keep = (ctx, stack, x, seq_offsets, positions, sel_idx, sel_count, scores, workspace)
+        h = C.c_void_p()
+        _check(load_library().qtale_graph_capture_stack(
+            ctx._h, C.byref(stack.cfg), stack._w, stack.n, _ptr(x), T, _ptr(seq_offsets), B, _ptr(positions),
+            stack._kv, _ptr(sel_idx), _ptr(sel_count), _ptr(scores), _ptr(workspace), workspace.numel(),
+            C.byref(h)), "qtale_graph_capture_stack")
+        self._h = h
+
+    def launch(self):
+        _check(load_library().qtale_graph_launch(self._h, _stream()), "qtale_graph_launch")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().qtale_graph_destroy(self._h)
+            self._h = None
 
 
 def qtale_router_select(ctx, x, router_w, router_b=0.0, seq_offsets=None):

@@ -591,6 +591,68 @@ int qtale_swiglu_w4a16(const qtale_qlinear* gate, const qtale_qlinear* up, int b
     return QTALE_OK;
 }
 
+// ---- HIP graph of one stack forward ---------------------------------------------------------------------------
+struct qtale_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipStream_t capture_stream = nullptr;
+};
+
+void qtale_graph_destroy(qtale_graph* g) {
+    if (!g) return;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    if (g->capture_stream) (void)hipStreamDestroy(g->capture_stream);
+    delete g;
+}
+
+int qtale_graph_capture_stack(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* layers,
+                              int n_layers, void* x, int T, const int32_t* seq_offsets, int B,
+                              const int32_t* positions, const qtale_kv* kv_per_layer, int32_t* sel_idx,
+                              int32_t* sel_count, float* scores, void* workspace, size_t workspace_bytes,
+                              qtale_graph** out) {
+    if (!out) return QTALE_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!ctx || ctx->profiling) return QTALE_ERR_INVALID_ARG;       // event spans cannot be recorded into a graph
+    // validate everything before capture starts, so that a failing call never leaves a capture open
+    int e = check_forward_args(ctx, cfg, x, T, seq_offsets, B, positions, workspace, workspace_bytes);
+    if (e) return e;
+    if (n_layers <= 0 || !layers || T <= 0) return QTALE_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+        if ((e = check_weights(cfg, &layers[l]))) return e;
+        if (kv_per_layer && (e = check_kv(&kv_per_layer[l]))) return e;
+    }
+    qtale_graph* g = new (std::nothrow) qtale_graph();
+    if (!g) return QTALE_ERR_HIP;
+    if (hipStreamCreateWithFlags(&g->capture_stream, hipStreamNonBlocking) != hipSuccess) {
+        qtale_graph_destroy(g);
+        return QTALE_ERR_HIP;
+    }
+    if (hipStreamBeginCapture(g->capture_stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+        qtale_graph_destroy(g);
+        return QTALE_ERR_HIP;
+    }
+    e = qtale_stack_forward(ctx, cfg, layers, n_layers, x, T, seq_offsets, B, positions, kv_per_layer, sel_idx,
+                            sel_count, scores, nullptr, workspace, workspace_bytes, g->capture_stream);
+    const hipError_t he = hipStreamEndCapture(g->capture_stream, &g->graph);   // always close the capture
+    if (e || he != hipSuccess || !g->graph) {
+        qtale_graph_destroy(g);
+        return e ? e : QTALE_ERR_HIP;
+    }
+    if (hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0) != hipSuccess) {
+        qtale_graph_destroy(g);
+        return QTALE_ERR_HIP;
+    }
+    *out = g;
+    return QTALE_OK;
+}
+
+int qtale_graph_launch(qtale_graph* g, void* stream) {
+    if (!g || !g->exec) return QTALE_ERR_INVALID_ARG;
+    HIP_TRY(hipGraphLaunch(g->exec, reinterpret_cast<hipStream_t>(stream)));
+    return QTALE_OK;
+}
+
 int qtale_profile_enable(qtale_ctx* ctx, int on) {
     if (!ctx) return QTALE_ERR_INVALID_ARG;
     ctx->profiling = on != 0;
