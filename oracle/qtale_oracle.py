@@ -175,6 +175,23 @@ def router_scores(x, w, b=0.0):
     return z.astype(np.float32)
 
 
+def router_scores_mlp(x, W1, b1, W2, b2):
+    """Two-output MLP router (Sec. 2.2: the router is a lightweight MLP with two outputs; Eq. 9 applies a
+    softmax to them).  The paper states neither depth, width nor activation; this reading is one hidden
+    layer with ReLU:  u = relu(W1 x + b1),  (l_e, l_b) = W2 u + b2,  and since the softmax over two classes
+    gives p_0 = sigmoid(l_e - l_b), the score is z = l_e - l_b.  Everything in fp64, one rounding to fp32.
+
+    x [T, H]; W1 [R, H], b1 [R], W2 [2, R], b2 [2], all fp32 parameters."""
+    x = np.asarray(x, dtype=np.float64)
+    W1 = np.asarray(W1, dtype=np.float32).astype(np.float64)
+    b1 = np.asarray(b1, dtype=np.float32).astype(np.float64)
+    W2 = np.asarray(W2, dtype=np.float32).astype(np.float64)
+    b2 = np.asarray(b2, dtype=np.float32).astype(np.float64)
+    u = np.maximum(x @ W1.T + b1, 0.0)
+    logits = u @ W2.T + b2
+    return (logits[:, 0] - logits[:, 1]).astype(np.float32)
+
+
 def execute_probability(z):
     """p_0 of Eq. 9 for the two-class softmax over (z_e, z_b) with z = z_e - z_b."""
     z = np.asarray(z, dtype=np.float64)
@@ -252,13 +269,14 @@ def silu(a):
 class LayerParams:
     """Dequantized fp64 weights of one layer plus gains and router."""
 
-    def __init__(self, Wq, Wk, Wv, Wo, Wg, Wu, Wd, g1, g2, router_w, router_b=0.0):
+    def __init__(self, Wq, Wk, Wv, Wo, Wg, Wu, Wd, g1, g2, router_w, router_b=0.0, router_mlp=None):
         self.Wq, self.Wk, self.Wv, self.Wo = Wq, Wk, Wv, Wo
         self.Wg, self.Wu, self.Wd = Wg, Wu, Wd
         self.g1 = np.asarray(g1, dtype=np.float64)
         self.g2 = np.asarray(g2, dtype=np.float64)
         self.router_w = np.asarray(router_w, dtype=np.float32)
         self.router_b = float(router_b)
+        self.router_mlp = router_mlp        # None (linear router) or (W1, b1, W2, b2) of the two-output MLP
 
 
 class KVCache:
@@ -279,7 +297,10 @@ def _seq_of(t, seq_offsets):
 
 def decide(x, p, mode, control):
     """Scores and ascending executed indices for one layer."""
-    z = router_scores(x, p.router_w, p.router_b)
+    if getattr(p, "router_mlp", None) is not None:
+        z = router_scores_mlp(x, *p.router_mlp)
+    else:
+        z = router_scores(x, p.router_w, p.router_b)
     if mode == "ratio":
         idx = select_ratio(z, control)
     elif mode == "threshold":

@@ -103,3 +103,75 @@ def test_executed_count_rounding():
     assert orc.executed_count(0.6, 16384) == 9830
     assert [orc.executed_count(r, 64) for r in (1.0, 0.8, 0.6, 0.4)] == [64, 51, 38, 26]
     assert orc.executed_count(0.5, 1) == 1 and orc.executed_count(0.49, 1) == 0
+
+
+# ---- two-output MLP router (Sec. 2.2 / Eq. 9) ------------------------------------------------------------
+
+def _mlp(H, R, seed):
+    rng = np.random.default_rng(seed)
+    return ((rng.standard_normal((R, H)) * 0.05).astype(np.float32), (rng.standard_normal(R) * 0.1).astype(np.float32),
+            (rng.standard_normal((2, R)) * 0.5).astype(np.float32), (rng.standard_normal(2) * 0.1).astype(np.float32))
+
+
+def test_mlp_router_matches_exact_rational_arithmetic():
+    # fp16 activations and fp32 parameters are dyadic rationals: Fraction arithmetic is exact, and the fp64
+    # path may differ from it by fp64 rounding only (far below the fp32 rounding of the score)
+    from fractions import Fraction
+    H, R, T = 12, 5, 7
+    W1, b1, W2, b2 = _mlp(H, R, 0)
+    x = np.random.default_rng(1).standard_normal((T, H)).astype(np.float16).astype(np.float64)
+    z = orc.router_scores_mlp(x, W1, b1, W2, b2)
+    for t in range(T):
+        u = []
+        for r in range(R):
+            acc = Fraction(float(b1[r]))
+            for k in range(H):
+                acc += Fraction(float(W1[r, k])) * Fraction(float(x[t, k]))
+            u.append(max(acc, Fraction(0)))
+        le = Fraction(float(b2[0])) + sum(Fraction(float(W2[0, r])) * u[r] for r in range(R))
+        lb = Fraction(float(b2[1])) + sum(Fraction(float(W2[1, r])) * u[r] for r in range(R))
+        exact = float(le - lb)
+        assert z[t] == np.float32(exact)                          # the exact value, rounded once to fp32
+
+
+def test_mlp_router_decision_equals_two_class_softmax():
+    H, R, T = 32, 8, 400
+    W1, b1, W2, b2 = _mlp(H, R, 2)
+    x = np.random.default_rng(3).standard_normal((T, H)).astype(np.float16).astype(np.float64)
+    z = orc.router_scores_mlp(x, W1, b1, W2, b2)
+    u = np.maximum(x @ W1.astype(np.float64).T + b1, 0)
+    logits = u @ W2.astype(np.float64).T + b2
+    e = np.exp(logits - logits.max(axis=1, keepdims=True))
+    p0 = e[:, 0] / e.sum(axis=1)                                  # Eq. 9 written out
+    for theta in (0.5, 0.3, 0.45):
+        want = np.nonzero(p0 >= theta)[0]
+        got = orc.select_threshold(z, theta)
+        near = np.nonzero(np.abs(p0 - theta) < 1e-6)[0]
+        assert set(want) - set(near) <= set(got) <= set(want) | set(near)
+    assert np.array_equal(orc.select_threshold(z, 0.5), np.nonzero(logits[:, 0] >= logits[:, 1])[0])   # arg-max rule, Eq. 2
+
+
+def test_mlp_router_with_one_always_active_unit_is_the_linear_router():
+    # R = 1, a large positive b1 keeps the ReLU open: z = w2 (w1.x + b1) + b2 is affine in x
+    H, T = 16, 50
+    rng = np.random.default_rng(4)
+    w = (rng.standard_normal(H) * 0.1).astype(np.float32)
+    x = rng.standard_normal((T, H)).astype(np.float16).astype(np.float64)
+    W1, b1 = w[None, :], np.array([64.0], dtype=np.float32)
+    W2, b2 = np.array([[1.0], [0.0]], dtype=np.float32), np.array([-64.0, 0.0], dtype=np.float32)
+    z = orc.router_scores_mlp(x, W1, b1, W2, b2)
+    lin = orc.router_scores(x, w, 0.0)
+    assert np.max(np.abs(z - lin)) <= 64.0 * 2.0 ** -50           # 64 is added and removed in fp64
+
+
+def test_layer_uses_the_mlp_router_when_given():
+    from tests.helpers import TINY, cfg_dict, oracle_layer, to_f64
+    import synth_inputs as si
+    p, _ = oracle_layer(TINY, 0, 6)
+    p.router_mlp = _mlp(TINY.hidden, 4, 5)
+    x = to_f64(si.hidden_states(TINY, 20, 6))
+    offs, pos = si.equal_sequences(1, 20)
+    _, idx, z = orc.layer_forward(x, p, cfg_dict(TINY), offs.numpy(), pos.numpy(), "ratio", 0.5)
+    assert np.array_equal(z, orc.router_scores_mlp(x, *p.router_mlp))
+    assert np.array_equal(idx, orc.select_ratio(z, 0.5))
+
