@@ -328,6 +328,32 @@ def main():
                      "fresh_batch_ratio": float(cnt.sum().item()) / (L * T),
                      "tokens_per_s": T / dt_thr, "ms_per_step": dt_thr * 1e3}
         qt.qtale_set_exec_ratio(ctx, args.ratio)
+    # the same stack with the paper's two-output MLP router (one hidden ReLU layer of 16 units) instead of the
+    # linear one
+    mlp = None
+    if not args.no_sweep:
+        mlp_layers = [qt.LayerWeights(lw.lin["q"], lw.lin["k"], lw.lin["v"], lw.lin["o"], lw.lin["gate"], lw.lin["up"],
+                                      lw.lin["down"], lw.norm1, lw.norm2, None, 0.0,
+                                      si.router_mlp(shape, l, 0, 16, device=dev)) for l, lw in enumerate(layers)]
+        mlp_stack = qt.Stack(cfg, mlp_layers)
+        xs = batches(4, 6000)
+        qt.qtale_stack_forward(ctx, mlp_stack, xs[0], offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for x in xs[1:]:
+            qt.qtale_stack_forward(ctx, mlp_stack, x, offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        dt_mlp = (time.perf_counter() - t0) / 3
+        xs = batches(1, 6100)
+        qt.qtale_profile_enable(ctx, True)
+        qt.qtale_stack_forward(ctx, mlp_stack, xs[0], offs, pos, workspace=ws)
+        prof_mlp = qt.qtale_profile_read(ctx)
+        qt.qtale_profile_enable(ctx, False)
+        r_ms = prof_mlp["router"][0] / prof_mlp["router"][1]
+        mlp = {"router": "two-output MLP, 16 hidden ReLU units, fp64 accumulation", "tokens_per_s": T / dt_mlp,
+               "ms_per_step": dt_mlp * 1e3, "router_kernel_ms": r_ms,
+               "router_fp64_TFLOPs": 2.0 * T * shape.hidden * 16 / (r_ms * 1e-3) / 1e12}
+        del mlp_stack, mlp_layers
     del xs, ws
     int3 = None
     if not args.no_int3:
@@ -352,6 +378,7 @@ def main():
         "kernel_ms_per_launch": kern_ms,
         "tokens_per_s_vs_exec_ratio": sweep,
         "threshold_mode": threshold,
+        "mlp_router": mlp,
         "decode": decode,
         "int3": int3,
     }

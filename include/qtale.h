@@ -112,6 +112,15 @@ typedef struct {
     const void* norm2;                         /* [hidden], act dtype: gain of the pre-MLP RMSNorm */
     const float* router_w;                     /* [hidden] fp32: z_t = router_w . x_t + router_b */
     float router_b;
+    /* Optional two-output MLP router (Sec. 2.2), used instead of router_w/router_b when router_hidden > 0:
+     * u = relu(W1 x_t + b1), (l_e, l_b) = W2 u + b2, z_t = l_e - l_b (p_0 of Eq. 9 = sigmoid(z_t)); fp64 sums,
+     * one rounding to fp32.  The paper gives no depth, width or activation: one hidden ReLU layer is this
+     * library's reading.  router_hidden in 1..256; router_w may then be NULL. */
+    int router_hidden;                         /* R; 0 = linear router */
+    const float* router_w1;                    /* [R][hidden] fp32 */
+    const float* router_b1;                    /* [R] fp32 */
+    const float* router_w2;                    /* [2][R] fp32: row 0 execute logit, row 1 bypass logit */
+    const float* router_b2;                    /* [2] fp32 */
 } qtale_layer_weights;
 
 /* Per-layer K/V cache holding entries of EXECUTED tokens only (a bypassed token produces no key or
@@ -192,6 +201,10 @@ int qtale_calibrate_threshold(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const 
                               const int32_t* seq_offsets, int B, const int32_t* positions, float target_ratio,
                               void* scratch, void* workspace, size_t workspace_bytes,
                               float* theta, float* ratio, float* table, void* stream);
+
+/* Scores of the two-output MLP router alone (see qtale_layer_weights): scores[t] for T tokens. */
+int qtale_router_mlp_scores(int act_dtype, const void* x, int T, int hidden, const float* w1, const float* b1,
+                            const float* w2, const float* b2, int router_hidden, float* scores /*[T]*/, void* stream);
 
 /* out[M][N] (fp16) = A[M][K] (fp16) x dequant(W)^T for one quantized linear (matrix-core GEMM on 4-bit or
  * 3-bit codes, `bits`/`group` as given to qtale_quantize for this matrix). */

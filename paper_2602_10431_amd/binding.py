@@ -24,7 +24,7 @@ EXPORTS = ["qtale_strerror", "qtale_create", "qtale_destroy", "qtale_set_exec_ra
            "qtale_workspace_bytes", "qtale_layer_forward", "qtale_stack_forward", "qtale_router_select",
            "qtale_linear_w4a16", "qtale_swiglu_w4a16", "qtale_profile_enable", "qtale_profile_read",
            "qtale_calibration_scratch_bytes", "qtale_calibrate_threshold_from_scores", "qtale_calibrate_threshold",
-           "qtale_graph_capture_stack", "qtale_graph_launch", "qtale_graph_destroy"]
+           "qtale_graph_capture_stack", "qtale_graph_launch", "qtale_graph_destroy", "qtale_router_mlp_scores"]
 QTALE_THETA_GRID = 50
 
 
@@ -48,7 +48,9 @@ class qtale_qlinear(C.Structure):
 class qtale_layer_weights(C.Structure):
     _fields_ = [("q", qtale_qlinear), ("k", qtale_qlinear), ("v", qtale_qlinear), ("o", qtale_qlinear),
                 ("gate", qtale_qlinear), ("up", qtale_qlinear), ("down", qtale_qlinear),
-                ("norm1", C.c_void_p), ("norm2", C.c_void_p), ("router_w", C.c_void_p), ("router_b", C.c_float)]
+                ("norm1", C.c_void_p), ("norm2", C.c_void_p), ("router_w", C.c_void_p), ("router_b", C.c_float),
+                ("router_hidden", C.c_int), ("router_w1", C.c_void_p), ("router_b1", C.c_void_p),
+                ("router_w2", C.c_void_p), ("router_b2", C.c_void_p)]
 
 
 class qtale_kv(C.Structure):
@@ -95,6 +97,7 @@ def load_library():
                                               i, vp, i, vp, C.c_float, vp, vp, C.c_size_t, fp, fp, fp, vp]
     lib.qtale_graph_capture_stack.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, i, vp,
                                               i, vp, C.POINTER(qtale_kv), vp, vp, vp, vp, C.c_size_t, C.POINTER(vp)]
+    lib.qtale_router_mlp_scores.argtypes = [i, vp, i, i, vp, vp, vp, vp, i, vp, vp]
     lib.qtale_graph_launch.argtypes = [vp, vp]
     lib.qtale_graph_destroy.argtypes = [vp]
     lib.qtale_graph_destroy.restype = None
@@ -212,16 +215,25 @@ def qtale_prepack(codes, scales, zeros, N, K, bits=4, group=128):
 class LayerWeights:
     """Holds the device tensors of one layer and the matching C struct."""
 
-    def __init__(self, q, k, v, o, gate, up, down, norm1, norm2, router_w, router_b=0.0):
+    def __init__(self, q, k, v, o, gate, up, down, norm1, norm2, router_w, router_b=0.0, router_mlp=None):
+        """router_mlp: None (linear router) or (W1 [R,H], b1 [R], W2 [2,R], b2 [2]) fp32 CUDA tensors."""
         self.lin = dict(q=q, k=k, v=v, o=o, gate=gate, up=up, down=down)
         self.norm1, self.norm2, self.router_w, self.router_b = norm1, norm2, router_w, float(router_b)
+        self.router_mlp = router_mlp
+        if router_mlp is not None:
+            W1, b1, W2, b2 = router_mlp
+            for t in router_mlp:
+                assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+            assert W2.shape == (2, W1.shape[0]) and b1.shape == (W1.shape[0],) and b2.shape == (2,)
 
     def c_struct(self):
         l = self.lin
         return qtale_layer_weights(l["q"].c_struct(), l["k"].c_struct(), l["v"].c_struct(), l["o"].c_struct(),
                                    l["gate"].c_struct(), l["up"].c_struct(), l["down"].c_struct(),
-                                   self.norm1.data_ptr(), self.norm2.data_ptr(), self.router_w.data_ptr(),
-                                   self.router_b)
+                                   self.norm1.data_ptr(), self.norm2.data_ptr(),
+                                   self.router_w.data_ptr() if self.router_w is not None else None, self.router_b,
+                                   *((0, None, None, None, None) if self.router_mlp is None else
+                                     (self.router_mlp[0].shape[0],) + tuple(t.data_ptr() for t in self.router_mlp)))
 
 
 class KVCache:
@@ -315,6 +327,15 @@ def qtale_calibrate_threshold(ctx, stack, x_calib, seq_offsets, positions, targe
                                          _ptr(workspace), workspace.numel(), C.byref(theta), C.byref(ratio), table,
                                          _stream()), "qtale_calibrate_threshold")
     return _calibration_result(theta, ratio, table)
+
+
+def qtale_router_mlp_scores(x, W1, b1, W2, b2):
+    T, H = x.shape
+    scores = torch.empty(T, dtype=torch.float32, device=x.device)
+    _check(load_library().qtale_router_mlp_scores(_act_code(x.dtype), _ptr(x), T, H, _ptr(W1), _ptr(b1), _ptr(W2),
+                                                  _ptr(b2), W1.shape[0], _ptr(scores), _stream()),
+           "qtale_router_mlp_scores")
+    return scores
 
 
 class StackGraph:

@@ -113,8 +113,13 @@ int check_weights(const qtale_layer_cfg* c, const qtale_layer_weights* w) {
     if ((e = check_linear(w->gate, c->inter, H))) return e;
     if ((e = check_linear(w->up, c->inter, H))) return e;
     if ((e = check_linear(w->down, H, c->inter))) return e;
-    if (!w->norm1 || !w->norm2 || !w->router_w) return QTALE_ERR_INVALID_ARG;
-    if (std::isnan(w->router_b)) return QTALE_ERR_INVALID_ARG;
+    if (!w->norm1 || !w->norm2) return QTALE_ERR_INVALID_ARG;
+    if (w->router_hidden < 0 || w->router_hidden > 256) return QTALE_ERR_INVALID_ARG;
+    if (w->router_hidden > 0) {
+        if (!w->router_w1 || !w->router_b1 || !w->router_w2 || !w->router_b2) return QTALE_ERR_INVALID_ARG;
+    } else {
+        if (!w->router_w || std::isnan(w->router_b)) return QTALE_ERR_INVALID_ARG;
+    }
     return QTALE_OK;
 }
 
@@ -183,7 +188,11 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
 
     {
         Prof pr(ctx, stream, 0);
-        HIP_TRY(launch_router_score(x, bf16, T, H, w->router_w, w->router_b, z, stream));
+        if (w->router_hidden > 0)
+            HIP_TRY(launch_router_mlp(x, bf16, T, H, w->router_w1, w->router_b1, w->router_w2, w->router_b2,
+                                      w->router_hidden, z, stream));
+        else
+            HIP_TRY(launch_router_score(x, bf16, T, H, w->router_w, w->router_b, z, stream));
     }
     {
         Prof pr(ctx, stream, 1);
@@ -557,6 +566,18 @@ int qtale_calibrate_threshold(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const 
         return e;
     }
     return finish_calibration(ctx, table, best, theta, ratio, table_out);
+}
+
+int qtale_router_mlp_scores(int act_dtype, const void* x, int T, int hidden, const float* w1, const float* b1,
+                            const float* w2, const float* b2, int router_hidden, float* scores, void* stream) {
+    if (T < 0 || hidden <= 0 || router_hidden <= 0 || router_hidden > 256) return QTALE_ERR_INVALID_ARG;
+    if (act_dtype != QTALE_ACT_FP16 && act_dtype != QTALE_ACT_BF16) return QTALE_ERR_UNSUPPORTED;
+    if (hidden % 8 != 0) return QTALE_ERR_SHAPE;
+    if (T == 0) return QTALE_OK;
+    if (!x || !w1 || !b1 || !w2 || !b2 || !scores) return QTALE_ERR_INVALID_ARG;
+    HIP_TRY(launch_router_mlp(x, act_dtype == QTALE_ACT_BF16, T, hidden, w1, b1, w2, b2, router_hidden, scores,
+                              reinterpret_cast<hipStream_t>(stream)));
+    return QTALE_OK;
 }
 
 int qtale_linear_w4a16(const qtale_qlinear* w, int bits, int group, const void* A, int M, void* out, void* stream) {

@@ -21,6 +21,10 @@ hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const u
 hipError_t launch_router_score(const void* x, int bf16, int T, int H, const float* w, float b,
                                float* z, hipStream_t stream);
 
+// Two-output MLP router: z_t = (W2 relu(W1 x_t + b1) + b2)[0] - (...)[1]; W1 [R][H], b1 [R], W2 [2][R], b2 [2] fp32.
+hipError_t launch_router_mlp(const void* x, int bf16, int T, int H, const float* W1, const float* b1, const float* W2,
+                             const float* b2, int R, float* z, hipStream_t stream);
+
 struct SelectArgs {
     const float* z;            // [T]
     int T;

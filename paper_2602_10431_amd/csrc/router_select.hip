@@ -53,6 +53,208 @@ hipError_t launch_router_score(const void* x, int bf16, int T, int H, const floa
     return hipGetLastError();
 }
 
+// Two-output MLP router (Sec. 2.2: "lightweight MLP" with two outputs; Eq. 9 takes their softmax).  This
+// library's reading: one hidden ReLU layer,  u = relu(W1 x + b1),  (l_e, l_b) = W2 u + b2,  score
+// z = l_e - l_b (the two-class softmax gives p_0 = sigmoid(z)).  All sums in fp64, one rounding to fp32, so
+// the executed set is reproducible exactly as for the linear router.
+//
+// The first layer is a [T x H] x [H x R] product in fp64 on the vector ALUs.  A workgroup owns 16 tokens (four
+// per wave) and walks H in chunks of 512 columns: the W1 chunk of 4 hidden units is staged in LDS once per
+// workgroup (two buffers, the next chunk's global loads are issued before the current one is consumed, one
+// barrier per chunk), a lane holds 8 consecutive columns of its four tokens, and every staged weight is
+// converted to fp64 once and used for four tokens (16 accumulators of two registers each per lane, two
+// workgroups per CU; 8 units per pass would spill).  The walk repeats per group of 4 units (x then comes
+// from L2).
+constexpr int kMlpRC = 4;         // hidden units per pass
+constexpr int kMlpKC = 512;       // columns per staged chunk
+constexpr int kMlpTW = 4;         // tokens per wave
+constexpr int kMlpWL = (kMlpRC * kMlpKC / 4) / 256;   // float4 loads per thread per chunk
+
+template <bool BF16>
+__global__ void __launch_bounds__(256, 2)
+router_mlp_kernel(const uint16_t* __restrict__ x, int T, int H, const float* __restrict__ W1,
+                  const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ b2, int R,
+                  float* __restrict__ z) {
+    __shared__ __attribute__((aligned(16))) float Ws[2][kMlpRC][kMlpKC];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * (4 * kMlpTW) + wave * kMlpTW;
+    const uint16_t* xrow[kMlpTW];
+#pragma unroll
+    for (int i = 0; i < kMlpTW; ++i) xrow[i] = x + static_cast<size_t>(min(t0 + i, T - 1)) * H;
+
+    double le[kMlpTW], lb[kMlpTW];
+#pragma unroll
+    for (int i = 0; i < kMlpTW; ++i) { le[i] = 0.0; lb[i] = 0.0; }
+
+    float4 wreg[kMlpWL];
+    u32x4_t xreg[kMlpTW];
+    auto fetch = [&](int rc, int kb) {                         // global -> registers for chunk (rc, kb)
+#pragma unroll
+        for (int it = 0; it < kMlpWL; ++it) {
+            const int c = it * 256 + tid;
+            const int row = c / (kMlpKC / 4), col = (c % (kMlpKC / 4)) * 4;
+            wreg[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rc + row < R && kb + col < H)
+                wreg[it] = *reinterpret_cast<const float4*>(W1 + static_cast<size_t>(rc + row) * H + kb + col);
+        }
+        const int k = kb + lane * 8;
+#pragma unroll
+        for (int i = 0; i < kMlpTW; ++i) {
+            xreg[i] = u32x4_t{0u, 0u, 0u, 0u};
+            if (k < H) xreg[i] = *reinterpret_cast<const u32x4_t*>(xrow[i] + k);
+        }
+    };
+
+    const int n_kb = (H + kMlpKC - 1) / kMlpKC;
+    const int n_rc = (R + kMlpRC - 1) / kMlpRC;
+    const int n_chunks = n_rc * n_kb;                          // walked as one sequence: rc-major, kb-minor
+    fetch(0, 0);
+    int buf = 0;
+    double acc[kMlpTW][kMlpRC];
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int rc = (ch / n_kb) * kMlpRC, kbi = ch % n_kb;
+        if (kbi == 0) {
+#pragma unroll
+            for (int i = 0; i < kMlpTW; ++i)
+#pragma unroll
+                for (int r = 0; r < kMlpRC; ++r) acc[i][r] = 0.0;
+        }
+        // park this chunk's weights, expand this chunk's activations
+#pragma unroll
+        for (int it = 0; it < kMlpWL; ++it) {
+            const int c = it * 256 + tid;
+            *reinterpret_cast<float4*>(&Ws[buf][c / (kMlpKC / 4)][(c % (kMlpKC / 4)) * 4]) = wreg[it];
+        }
+        double xd[kMlpTW][8];
+#pragma unroll
+        for (int i = 0; i < kMlpTW; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xd[i][2 * j] = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xreg[i][j] & 0xffffu)));
+                xd[i][2 * j + 1] = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xreg[i][j] >> 16)));
+            }
+        __syncthreads();          // chunk staged; the other buffer (read in the previous iteration) is free again
+        if (ch + 1 < n_chunks) fetch(((ch + 1) / n_kb) * kMlpRC, ((ch + 1) % n_kb) * kMlpKC);
+#pragma unroll
+        for (int r = 0; r < kMlpRC; ++r) {
+            const float4 w0 = *reinterpret_cast<const float4*>(&Ws[buf][r][lane * 8]);
+            const float4 w1 = *reinterpret_cast<const float4*>(&Ws[buf][r][lane * 8 + 4]);
+            const double wd[8] = {static_cast<double>(w0.x), static_cast<double>(w0.y), static_cast<double>(w0.z),
+                                  static_cast<double>(w0.w), static_cast<double>(w1.x), static_cast<double>(w1.y),
+                                  static_cast<double>(w1.z), static_cast<double>(w1.w)};
+#pragma unroll
+            for (int i = 0; i < kMlpTW; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][r] = fma(xd[i][j], wd[j], acc[i][r]);
+        }
+        buf ^= 1;
+        if (kbi == n_kb - 1) {
+            // hidden units of this pass: full sums, bias, ReLU, then their share of the two logits (in unit order)
+#pragma unroll
+            for (int r = 0; r < kMlpRC; ++r) {
+                const bool live = rc + r < R;
+                const double bias = live ? static_cast<double>(b1[rc + r]) : 0.0;
+                const double we = live ? static_cast<double>(W2[rc + r]) : 0.0;
+                const double wb = live ? static_cast<double>(W2[R + rc + r]) : 0.0;
+#pragma unroll
+                for (int i = 0; i < kMlpTW; ++i) {
+                    const double u = fmax(wave_sum(acc[i][r]) + bias, 0.0);
+                    le[i] = fma(we, u, le[i]);
+                    lb[i] = fma(wb, u, lb[i]);
+                }
+            }
+        }
+    }
+    if (lane == 0) {
+        const double be = static_cast<double>(b2[0]), bb = static_cast<double>(b2[1]);
+#pragma unroll
+        for (int i = 0; i < kMlpTW; ++i)
+            if (t0 + i < T) z[t0 + i] = static_cast<float>((le[i] + be) - (lb[i] + bb));
+    }
+}
+
+// Few tokens (decode steps): one workgroup per token, the 256 threads split H (8 columns each per 2048-column
+// sweep) and read W1 straight from L2, 16 hidden units per pass with 4 units' loads in flight; the per-thread
+// partial sums meet in a wave reduction plus a four-entry LDS exchange.
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+router_mlp_small_kernel(const uint16_t* __restrict__ x, int T, int H, const float* __restrict__ W1,
+                        const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ b2, int R,
+                        float* __restrict__ z) {
+    constexpr int RG = 16;
+    __shared__ double part[4][RG];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = blockIdx.x;
+    const uint16_t* xr = x + static_cast<size_t>(t) * H;
+    double le = 0.0, lb = 0.0;
+    for (int rg = 0; rg < R; rg += RG) {
+        double acc[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r) acc[r] = 0.0;
+        for (int k = tid * 8; k < H; k += 2048) {
+            const u32x4_t xv = *reinterpret_cast<const u32x4_t*>(xr + k);
+            double xd[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xd[2 * j] = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xv[j] & 0xffffu)));
+                xd[2 * j + 1] = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xv[j] >> 16)));
+            }
+#pragma unroll
+            for (int r4 = 0; r4 < RG; r4 += 4) {
+                float4 w[4][2];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int r = min(rg + r4 + u, R - 1);     // rows past R repeat the last one; their sums are dropped
+                    const float4* wp = reinterpret_cast<const float4*>(W1 + static_cast<size_t>(r) * H + k);
+                    w[u][0] = wp[0];
+                    w[u][1] = wp[1];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float wf[8] = {w[u][0].x, w[u][0].y, w[u][0].z, w[u][0].w, w[u][1].x, w[u][1].y, w[u][1].z, w[u][1].w};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[r4 + u] = fma(xd[j], static_cast<double>(wf[j]), acc[r4 + u]);
+                }
+            }
+        }
+        __syncthreads();                                       // `part` of the previous group has been read
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const double v = wave_sum(acc[r]);
+            if (lane == 0) part[wave][r] = v;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int r = 0; r < RG && rg + r < R; ++r) {
+                const double sum = (part[0][r] + part[1][r]) + (part[2][r] + part[3][r]);
+                const double u = fmax(sum + static_cast<double>(b1[rg + r]), 0.0);
+                le = fma(static_cast<double>(W2[rg + r]), u, le);
+                lb = fma(static_cast<double>(W2[R + rg + r]), u, lb);
+            }
+        }
+    }
+    if (tid == 0) z[t] = static_cast<float>((le + static_cast<double>(b2[0])) - (lb + static_cast<double>(b2[1])));
+}
+
+hipError_t launch_router_mlp(const void* x, int bf16, int T, int H, const float* W1, const float* b1, const float* W2,
+                             const float* b2, int R, float* z, hipStream_t stream) {
+    if (T == 0) return hipSuccess;
+    const uint16_t* xp = reinterpret_cast<const uint16_t*>(x);
+    if (T <= 512) {                                            // too few tokens to fill the chip 16 per workgroup
+        if (bf16)
+            hipLaunchKernelGGL(router_mlp_small_kernel<true>, dim3(T), dim3(256), 0, stream, xp, T, H, W1, b1, W2, b2, R, z);
+        else
+            hipLaunchKernelGGL(router_mlp_small_kernel<false>, dim3(T), dim3(256), 0, stream, xp, T, H, W1, b1, W2, b2, R, z);
+        return hipGetLastError();
+    }
+    const dim3 grid((T + 4 * kMlpTW - 1) / (4 * kMlpTW)), block(256);
+    if (bf16)
+        hipLaunchKernelGGL(router_mlp_kernel<true>, grid, block, 0, stream, xp, T, H, W1, b1, W2, b2, R, z);
+    else
+        hipLaunchKernelGGL(router_mlp_kernel<false>, grid, block, 0, stream, xp, T, H, W1, b1, W2, b2, R, z);
+    return hipGetLastError();
+}
+
 // fp32 -> uint32 key whose unsigned order is the float order (-0 is first folded onto +0).
 __device__ __forceinline__ uint32_t order_key(float f) {
     f += 0.0f;

@@ -55,7 +55,7 @@ C5 = LayerShape(5120, 40, 40, 128, 13824, 4, 128, "bf16")      # LLaMA-13B-shape
 
 _SLOTS = {"q": 0, "k": 1, "v": 2, "o": 3, "gate": 4, "up": 5, "down": 6,
           "router_w": 7, "g1": 8, "g2": 9, "x": 10, "k_cache": 11, "v_cache": 12,
-          "x_step": 13, "misc": 14}
+          "x_step": 13, "misc": 14, "router_w1": 15, "router_b1": 16, "router_w2": 17, "router_b2": 18}
 
 
 def _gen(seed, layer, slot, extra=0, device="cpu"):
@@ -81,6 +81,17 @@ def linear_weight(shape: LayerShape, name, layer, seed, std=0.02, device="cpu"):
 def router_weight(shape: LayerShape, layer, seed, std=0.02, device="cpu"):
     return torch.randn(shape.hidden, generator=_gen(seed, layer, "router_w", device=device), dtype=torch.float32,
                        device=device) * std
+
+
+def router_mlp(shape: LayerShape, layer, seed, R=16, std1=0.02, std2=0.25, device="cpu"):
+    """Parameters (W1 [R,H], b1 [R], W2 [2,R], b2 [2]) of a two-output MLP router, all fp32 random draws.  With the
+    default spreads and N(0,1) inputs the execute-minus-bypass logit is of order 1 at H=4096."""
+    g = lambda slot: _gen(seed, layer, slot, device=device)
+    W1 = torch.randn(R, shape.hidden, generator=g("router_w1"), dtype=torch.float32, device=device) * std1
+    b1 = torch.randn(R, generator=g("router_b1"), dtype=torch.float32, device=device) * std1
+    W2 = torch.randn(2, R, generator=g("router_w2"), dtype=torch.float32, device=device) * std2
+    b2 = torch.randn(2, generator=g("router_b2"), dtype=torch.float32, device=device) * std1
+    return W1, b1, W2, b2
 
 
 def norm_gains(shape: LayerShape, layer, seed, unit=True):

@@ -160,3 +160,23 @@ def test_selection_is_deterministic(qt):
     b = qt.qtale_router_select(ctx, x, w)
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+def _mlp_router(H, R, seed):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(R, H, generator=g) * 0.05, torch.randn(R, generator=g) * 0.1,
+            torch.randn(2, R, generator=g) * 0.5, torch.randn(2, generator=g) * 0.1)
+
+
+@pytest.mark.parametrize("T,H,R,dtype", [(64, 256, 16, "fp16"), (1000, 512, 8, "bf16"), (5, 64, 1, "fp16"),
+                                         (300, 4096, 32, "bf16"), (17, 1024, 40, "fp16"), (2048, 4096, 16, "bf16")])
+def test_mlp_router_scores_are_bit_exact(qt, T, H, R, dtype):
+    # hidden widths below, at and above one 16-unit pass; H below and above one 512-column chunk; ragged token tail
+    shape = si.LayerShape(H, 1, 1, 64, 64, 4, 32, dtype)
+    x = si.hidden_states(shape, T, 70 + R)
+    W1, b1, W2, b2 = _mlp_router(H, R, T + R)
+    z = qt.qtale_router_mlp_scores(x.cuda(), W1.cuda(), b1.cuda(), W2.cuda(), b2.cuda())
+    torch.cuda.synchronize()
+    want = orc.router_scores_mlp(x.to(torch.float64).numpy(), W1.numpy(), b1.numpy(), W2.numpy(), b2.numpy())
+    assert np.array_equal(z.cpu().numpy().view(np.uint32), want.view(np.uint32))
+

@@ -98,6 +98,27 @@ def test_three_bit_decode_step(qt):
     _cache_case(qt, shape, [1] * 8, [37, 5, 100, 64, 1, 99, 12, 63], [37, 5, 100, 64, 1, 99, 12, 63], 128, 22, 0.6)
 
 
+@pytest.mark.parametrize("mode,val", [("ratio", 0.5), ("threshold", 0.5)])
+def test_layer_with_two_output_mlp_router(qt, mode, val):
+    # Sec. 2.2 router as an MLP with two outputs; theta = 0.5 is the arg-max rule of Eq. 2
+    shape = si.C1
+    T, seed, R = 150, 23, 24
+    tensors = si.layer_tensors(shape, 0, seed, unit_gains=False, std=0.08)
+    g = torch.Generator().manual_seed(seed)
+    tensors["router_mlp"] = (torch.randn(R, shape.hidden, generator=g) * 0.05, torch.randn(R, generator=g) * 0.1,
+                             torch.randn(2, R, generator=g) * 0.5, torch.randn(2, generator=g) * 0.1)
+    x = si.hidden_states(shape, T, seed)
+    offs, pos = si.ragged_sequences([90, 60])
+    got, idx, _ = _run_layer(qt, shape, tensors, x, offs, pos, mode, val)
+    p, _ = oracle_layer(shape, 0, seed, tensors=tensors)
+    p.router_mlp = tuple(t.numpy() for t in tensors["router_mlp"])
+    want, widx, _ = orc.layer_forward(to_f64(x), p, cfg_dict(shape), offs.numpy(), pos.numpy(), mode, val)
+    assert 0 < len(widx) < T and np.array_equal(idx, widx)
+    skipped = np.setdiff1d(np.arange(T), widx)
+    assert torch.equal(got[skipped], x[skipped])
+    assert orc.parity_error(to_f64(got)[widx], want[widx]) <= TOL
+
+
 def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     T = sum(lens)
     B = len(lens)
