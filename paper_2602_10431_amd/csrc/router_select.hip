@@ -262,8 +262,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kSelThreads = 1024;
-
+template <int kSelThreads>
 __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t v, uint32_t* wsum, uint32_t& total) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
 #pragma unroll
@@ -291,13 +290,41 @@ __device__ __forceinline__ uint32_t block_scan_inclusive(uint32_t v, uint32_t* w
 
 // One workgroup selects and compacts: four 8-bit radix passes find the k-th largest key, one ordered
 // pass writes ascending indices, the tail derives per-sequence counts and advances the cache lengths.
+// Everything that is touched more than once lives in LDS (keys of up to 16384 tokens, up to 2048 sequence
+// offsets, the per-thread prefix counts of the current chunk): a single workgroup has nothing to hide the
+// latency of dependent global loads with, and binary searches over global arrays used to dominate its time.
+constexpr int kSelKeyCache = 16384;
+constexpr int kSelOffCache = 2048;
+constexpr int kSelPer = 8;                       // consecutive tokens per thread in the ordered pass
+
+template <int kSelThreads>
 __global__ void __launch_bounds__(kSelThreads)
 select_compact_kernel(SelectArgs a) {
-    __shared__ uint32_t hist[256];
+    extern __shared__ uint32_t skeys[];           // T keys when T <= kSelKeyCache (sized at launch)
+    __shared__ int32_t soffs[kSelOffCache];
+    __shared__ int32_t scu[kSelOffCache];        // executed tokens before each sequence boundary
+    __shared__ uint32_t pre[kSelThreads];        // executed tokens before the thread's first token (whole call)
+    __shared__ uint32_t emask[kSelThreads];      // which of the thread's tokens execute
+    __shared__ uint32_t hist[2][256];            // radix pass p counts into hist[p & 1] while the other one is cleared
     __shared__ uint32_t wsum[kSelThreads / 64];
     __shared__ uint32_t s_prefix, s_krem;
     const int tid = threadIdx.x;
     const int T = a.T;
+    const bool keys_cached = T <= kSelKeyCache;
+    const bool offs_cached = a.B >= 0 && a.B + 1 <= kSelOffCache;
+    if (keys_cached)
+        for (int t = tid; t < T; t += kSelThreads) skeys[t] = order_key(a.z[t]);
+    if (offs_cached)
+        for (int b = tid; b <= a.B; b += kSelThreads) soffs[b] = a.seq_offsets[b];
+    for (int i = tid; i < 256; i += kSelThreads) hist[0][i] = 0u;
+    __syncthreads();
+    auto key_of = [&](int t) { return keys_cached ? skeys[t] : order_key(a.z[t]); };
+    auto off_of = [&](int b) { return offs_cached ? soffs[b] : a.seq_offsets[b]; };
+    auto put_cu = [&](int b, int v) {
+        if (offs_cached) scu[b] = v;
+        if (a.cu_exec) a.cu_exec[b] = v;
+    };
+
     uint32_t kth, need_eq;
     if (a.mode == 0) {
         if (a.k <= 0) {
@@ -307,15 +334,15 @@ select_compact_kernel(SelectArgs a) {
             uint32_t prefix = 0u, krem = static_cast<uint32_t>(a.k);
             for (int pass = 0; pass < 4; ++pass) {
                 const int shift = 24 - 8 * pass;
-                if (tid < 256) hist[tid] = 0u;
-                __syncthreads();
+                uint32_t* h = hist[pass & 1];
+                for (int i = tid; i < 256; i += kSelThreads) hist[(pass + 1) & 1][i] = 0u;
                 for (int t = tid; t < T; t += kSelThreads) {
-                    const uint32_t key = order_key(a.z[t]);
-                    if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                    const uint32_t key = key_of(t);
+                    if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&h[(key >> shift) & 255u], 1u);
                 }
                 __syncthreads();
                 if (tid < 64) {
-                    const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+                    const uint32_t h0 = h[4 * tid], h1 = h[4 * tid + 1], h2 = h[4 * tid + 2], h3 = h[4 * tid + 3];
                     const uint32_t s = h0 + h1 + h2 + h3;
                     uint32_t suf = s;                        // inclusive sum over lanes >= tid
 #pragma unroll
@@ -335,10 +362,9 @@ select_compact_kernel(SelectArgs a) {
                         s_krem = krem - cum;
                     }
                 }
-                __syncthreads();
-                prefix = s_prefix;
+                __syncthreads();                             // s_prefix / s_krem are rewritten only after the next
+                prefix = s_prefix;                           // pass's first barrier
                 krem = s_krem;
-                __syncthreads();
             }
             kth = prefix;
             need_eq = krem;
@@ -348,70 +374,98 @@ select_compact_kernel(SelectArgs a) {
         need_eq = 0x7fffffffu;
     }
 
+    // Ordered compaction.  A thread owns `per` (up to 8) consecutive tokens, so one block scan of the per-thread
+    // counts (executed-by-score in the low half, ties in the high half) orders a chunk of threads x per tokens.  The
+    // thread's prefix count and execute mask stay in LDS for the boundary pass below: the executed tokens
+    // before a sequence boundary are the prefix of the thread that owns the boundary token plus the set bits
+    // below it, so no search over the index list is needed.
+    const int per = min(kSelPer, (T + kSelThreads - 1) / kSelThreads);
     uint32_t base_gt = 0u, base_eq = 0u;
-    for (int c0 = 0; c0 < T; c0 += kSelThreads) {
-        const int t = c0 + tid;
-        uint32_t gt = 0u, eq = 0u;
-        if (t < T) {
-            const uint32_t key = order_key(a.z[t]);
-            gt = key > kth ? 1u : 0u;
-            eq = key == kth ? 1u : 0u;
+    for (int c0 = 0; c0 < T; c0 += kSelThreads * per) {
+        const int t0 = c0 + tid * per;
+        uint32_t gtm = 0u, eqm = 0u;
+#pragma unroll
+        for (int j = 0; j < kSelPer; ++j) {
+            if (j < per && t0 + j < T) {
+                const uint32_t key = key_of(t0 + j);
+                gtm |= (key > kth ? 1u : 0u) << j;
+                eqm |= (key == kth ? 1u : 0u) << j;
+            }
         }
-        const uint32_t packed = gt | (eq << 16);
+        const uint32_t packed = static_cast<uint32_t>(__popc(gtm)) | (static_cast<uint32_t>(__popc(eqm)) << 16);
         uint32_t total;
-        const uint32_t excl = block_scan_inclusive(packed, wsum, total) - packed;
-        const uint32_t gt_before = base_gt + (excl & 0xffffu);
-        const uint32_t eq_before = base_eq + (excl >> 16);
-        if (gt || (eq && eq_before < need_eq)) {
-            const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-            a.idx[pos] = t;
-            if (a.idx_copy) a.idx_copy[pos] = t;
+        const uint32_t excl = block_scan_inclusive<kSelThreads>(packed, wsum, total) - packed;
+        uint32_t gt_before = base_gt + (excl & 0xffffu);
+        uint32_t eq_before = base_eq + (excl >> 16);
+        pre[tid] = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+        int seq = -1;                                       // sequence of the previous executed token of this thread
+        uint32_t em = 0u;
+#pragma unroll
+        for (int j = 0; j < kSelPer; ++j) {
+            const uint32_t gt = (gtm >> j) & 1u, eq = (eqm >> j) & 1u;
+            if (gt || (eq && eq_before < need_eq)) {
+                const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+                const int t = t0 + j;
+                em |= 1u << j;
+                a.idx[pos] = t;
+                if (a.idx_copy) a.idx_copy[pos] = t;
+                if (a.row_seq) {
+                    if (seq < 0 || off_of(seq + 1) <= t) {  // left the previous token's sequence: search again
+                        int lo = 0, hi = a.B;               // last b with seq_offsets[b] <= t
+                        while (lo + 1 < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            if (off_of(mid) <= t) lo = mid; else hi = mid;
+                        }
+                        seq = lo;
+                    }
+                    a.row_seq[pos] = seq;
+                }
+            }
+            gt_before += gt;
+            eq_before += eq;
+        }
+        emask[tid] = em;
+        __syncthreads();
+        // sequence boundaries that fall into this chunk
+        {
+            const int c1 = min(c0 + kSelThreads * per, T);
+            for (int b = tid; b <= a.B; b += kSelThreads) {
+                const int o = off_of(b);
+                if (o >= c0 && o < c1) {
+                    const int owner = (o - c0) / per, below = (o - c0) % per;
+                    put_cu(b, static_cast<int>(pre[owner] + __popc(emask[owner] & ((1u << below) - 1u))));
+                }
+            }
         }
         base_gt += total & 0xffffu;
         base_eq += total >> 16;
+        __syncthreads();                                    // pre / emask are rewritten by the next chunk
     }
     const int count = static_cast<int>(base_gt + (base_eq < need_eq ? base_eq : need_eq));
     if (tid == 0) {
         *a.count = count;
         if (a.count_copy) *a.count_copy = count;
     }
-    __threadfence_block();
+    for (int b = tid; b <= a.B; b += kSelThreads)
+        if (off_of(b) >= T) put_cu(b, count);               // boundaries at the end of the call
     __syncthreads();
-
-    // executed tokens before each sequence boundary: lower_bound(idx, seq_offsets[b])
-    auto lower_bound_idx = [&](int v) {
-        int lo = 0, hi = count;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (a.idx[mid] < v) lo = mid + 1; else hi = mid;
-        }
-        return lo;
-    };
-    for (int b = tid; b <= a.B; b += kSelThreads) {
-        const int cb = lower_bound_idx(a.seq_offsets[b]);
-        if (a.cu_exec) a.cu_exec[b] = cb;
-        if (a.kv_len && b < a.B) {
-            const int cn = lower_bound_idx(a.seq_offsets[b + 1]);
+    if (a.kv_len) {                                         // cu_exec is given whenever the sequence table is too long for LDS
+        for (int b = tid; b < a.B; b += kSelThreads) {
+            const int cb = offs_cached ? scu[b] : a.cu_exec[b];
+            const int cn = offs_cached ? scu[b + 1] : a.cu_exec[b + 1];
             const int old = a.kv_len[b];
             a.kv_old[b] = old;
             a.kv_len[b] = old + (cn - cb);
         }
     }
-    if (a.row_seq) {
-        for (int i = tid; i < count; i += kSelThreads) {
-            const int t = a.idx[i];
-            int lo = 0, hi = a.B;                           // last b with seq_offsets[b] <= t
-            while (lo + 1 < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (a.seq_offsets[mid] <= t) lo = mid; else hi = mid;
-            }
-            a.row_seq[i] = lo;
-        }
-    }
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
-    hipLaunchKernelGGL(select_compact_kernel, dim3(1), dim3(kSelThreads), 0, stream, a);
+    const size_t key_bytes = a.T <= kSelKeyCache ? static_cast<size_t>(a.T > 0 ? a.T : 0) * 4 : 0;
+    if (a.T <= 2048)       // few tokens (decode steps): four waves, cheaper barriers
+        hipLaunchKernelGGL(select_compact_kernel<256>, dim3(1), dim3(256), key_bytes, stream, a);
+    else
+        hipLaunchKernelGGL(select_compact_kernel<1024>, dim3(1), dim3(1024), key_bytes, stream, a);
     return hipGetLastError();
 }
 
