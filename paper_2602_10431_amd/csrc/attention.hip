@@ -29,8 +29,9 @@ struct AttnDev {
     const int32_t* count;
     const int32_t* cu_exec;
     const int32_t* row_seq;
-    const int2* items;           // prefill work list: (sequence, query tile)
+    const int4* items;           // prefill work list: (sequence or -1, query tile, first compact row, rows) per item
     const int32_t* n_items;
+    int items_max;               // host bound on the number of work items (row stride of the logical grid)
     const half_t* k_cache;
     const half_t* v_cache;
     const int32_t* kv_old;
@@ -51,13 +52,21 @@ flash_prefill_kernel(AttnDev p) {
     __shared__ __attribute__((aligned(16))) half_t Ks2[2][64 * KSTR];    // double-buffered tiles
     __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VSTR];
 
-    const int item = blockIdx.x;
-    if (item >= *p.n_items) return;
-    const int b = p.items[item].x, qt = p.items[item].y;
-    const int h = blockIdx.y;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Logical index L = head *
+    // items_max + item is laid out so that every XCD gets one contiguous range of L: the query tiles of one
+    // (sequence, head) read the same keys and values and now run on the same XCD at the same time, so its L2
+    // serves all but the first of them (each pair used to be fetched once per query tile from the fabric).
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int h = L / p.items_max;
+    const int item = L - h * p.items_max;
+    if (h >= p.nh) return;
+    const int4 it = p.items[item];           // one load tells the workgroup everything (unused slots hold -1)
+    const int b = it.x, qt = it.y;
+    if (b < 0) return;
     const int hk = h / (p.nh / p.nkv);
-    const int row_begin = p.cu_exec[b];
-    const int n_b = p.cu_exec[b + 1] - row_begin;
+    const int row_begin = it.z;
+    const int n_b = it.w;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
 
@@ -107,8 +116,9 @@ flash_prefill_kernel(AttnDev p) {
     // global -> register staging of one tile.  K: chunk c is key c / CPR, 8 halves at (c % CPR)*8.
     // V: a thread owns 4 consecutive keys x 8 columns and transposes them in registers, so that the
     // transposed tile Vt[column][key] is written with 8-byte stores.
-    u32x4_t kreg[CH], vreg[VG][4];
-    auto fetch = [&](int tile) {
+    // Two register sets: tile t+1 waits in one while tile t+2 is still in flight into the other.
+    u32x4_t kregs[2][CH], vregs[2][VG][4];
+    auto fetch = [&](int tile, u32x4_t* kreg, u32x4_t (*vreg)[4]) {
         const int key0 = tile * 64;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -127,7 +137,7 @@ flash_prefill_kernel(AttnDev p) {
             }
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, const u32x4_t* kreg, const u32x4_t (*vreg)[4]) {
         half_t* Ks = Ks2[buf];
         half_t* Vt = Vt2[buf];
 #pragma unroll
@@ -154,15 +164,17 @@ flash_prefill_kernel(AttnDev p) {
         }
     };
 
-    // Tile t+1 is parked in the other LDS buffer and tile t+2 requested before tile t is computed: one
-    // barrier per tile, and the staging of one wave overlaps the MFMAs of the others.
-    fetch(0);
-    stage(0);
-    if (n_tiles > 1) fetch(1);
+    // Tile t+1 is parked in the other LDS buffer and tile t+3 requested before tile t is computed (tile t+2 is
+    // already on its way): one barrier per tile, two tile times to cover the latency of a fetch, and the
+    // staging of one wave overlaps the MFMAs of the others.
+    fetch(0, kregs[0], vregs[0]);
+    stage(0, kregs[0], vregs[0]);
+    if (n_tiles > 1) fetch(1, kregs[1], vregs[1]);
+    if (n_tiles > 2) fetch(2, kregs[0], vregs[0]);
     __syncthreads();
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        if (tile + 1 < n_tiles) stage((tile + 1) & 1);
-        if (tile + 2 < n_tiles) fetch(tile + 2);
+    auto tile_step = [&](int tile, u32x4_t* kreg, u32x4_t (*vreg)[4]) {   // kreg/vreg: the set that holds tile + 1
+        if (tile + 1 < n_tiles) stage((tile + 1) & 1, kreg, vreg);
+        if (tile + 3 < n_tiles) fetch(tile + 3, kreg, vreg);
         const half_t* Ks = Ks2[tile & 1];
         const half_t* Vt = Vt2[tile & 1];
         const int key0 = tile * 64;
@@ -234,6 +246,10 @@ flash_prefill_kernel(AttnDev p) {
             }
         }
         __syncthreads();
+    };
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        tile_step(tile, kregs[1], vregs[1]);
+        if (tile + 1 < n_tiles) tile_step(tile + 1, kregs[0], vregs[0]);
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -252,9 +268,12 @@ flash_prefill_kernel(AttnDev p) {
     }
 }
 
-// Builds the prefill work list: one item per (sequence, tile of kAttnBQ executed rows).
+// Builds the prefill work list: one item per (sequence, tile of kAttnBQ executed rows), carrying the sequence's
+// first compact row and row count so that the attention workgroups need no further lookups; the slots up to
+// items_max that no tile uses are marked with sequence -1.
 __global__ void __launch_bounds__(256)
-attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int2* __restrict__ items, int32_t* __restrict__ n_items) {
+attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int4* __restrict__ items, int items_max,
+                  int32_t* __restrict__ n_items) {
     __shared__ int s_wave[4];
     __shared__ int s_base;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -262,7 +281,9 @@ attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int2* __restrict__
     __syncthreads();
     for (int b0 = 0; b0 < B; b0 += 256) {
         const int b = b0 + threadIdx.x;
-        const int nt = b < B ? (cu_exec[b + 1] - cu_exec[b] + kAttnBQ - 1) / kAttnBQ : 0;
+        const int first = b < B ? cu_exec[b] : 0;
+        const int rows = b < B ? cu_exec[b + 1] - first : 0;
+        const int nt = (rows + kAttnBQ - 1) / kAttnBQ;
         int incl = nt;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -273,12 +294,14 @@ attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int2* __restrict__
         __syncthreads();
         int start = s_base + incl - nt;
         for (int w = 0; w < wave; ++w) start += s_wave[w];
-        for (int q = 0; q < nt; ++q) items[start + q] = make_int2(b, nt - 1 - q);   // longest tiles first
+        for (int q = 0; q < nt; ++q) items[start + q] = make_int4(b, nt - 1 - q, first, rows);   // longest tiles first
         __syncthreads();
         if (threadIdx.x == 0) s_base += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *n_items = s_base;
+    const int used = s_base;
+    for (int i = used + threadIdx.x; i < items_max; i += 256) items[i] = make_int4(-1, 0, 0, 0);
+    if (threadIdx.x == 0) *n_items = used;
 }
 
 // Decode-style attention: workgroup = (executed row, kv head); REP query heads share the kv head.
@@ -435,7 +458,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
     d.count = a.count;
     d.cu_exec = a.cu_exec;
     d.row_seq = a.row_seq;
-    d.items = reinterpret_cast<const int2*>(a.items);
+    d.items = reinterpret_cast<const int4*>(a.items);
     d.n_items = a.n_items;
     d.k_cache = reinterpret_cast<const half_t*>(a.k_cache);
     d.v_cache = reinterpret_cast<const half_t*>(a.v_cache);
@@ -448,12 +471,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
         return a.d == 128 ? launch_decode_d<128>(d, rep, a.max_rows, a.nkv, stream)
                           : launch_decode_d<64>(d, rep, a.max_rows, a.nkv, stream);
     }
+    const int items_max = (a.max_rows + kAttnBQ - 1) / kAttnBQ + a.B;
+    d.items_max = items_max;
     hipLaunchKernelGGL(attn_items_kernel, dim3(1), dim3(256), 0, stream, a.cu_exec, a.B,
-                       reinterpret_cast<int2*>(a.items), a.n_items);
+                       reinterpret_cast<int4*>(a.items), items_max, a.n_items);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int items_max = (a.max_rows + kAttnBQ - 1) / kAttnBQ + a.B;
-    const dim3 grid(items_max, a.nh), block(256);
+    const dim3 grid(8 * ((items_max * a.nh + 7) / 8)), block(256);
     if (a.d == 128)
         hipLaunchKernelGGL(flash_prefill_kernel<128>, grid, block, 0, stream, d);
     else

@@ -64,7 +64,7 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
     w.cu_exec = reinterpret_cast<int32_t*>(take((static_cast<size_t>(B) + 1) * 4));
     w.row_seq = reinterpret_cast<int32_t*>(take(Tz * 4));
     w.kv_old = reinterpret_cast<int32_t*>(take(static_cast<size_t>(B) * 4 + 4));
-    w.items = take((Tz / kAttnBQ + B + 2) * 8);
+    w.items = take((Tz / kAttnBQ + B + 2) * 16);
     w.nbuf = take(Tz * c->hidden * 2);
     w.qkv = take(Tz * (static_cast<size_t>(c->n_heads) + 2 * c->n_kv_heads) * c->head_dim * 2);
     w.attn = take(Tz * c->n_heads * c->head_dim * 2);

@@ -113,7 +113,7 @@ struct AttnArgs {
     const void* k_cache; const void* v_cache; int cap;
     const int32_t* kv_old;     // [B]
     int T;                     // tokens in the call
-    void* items;               // scratch: (max_rows / kAttnBQ + B) x int2 work list of the prefill kernel
+    void* items;               // scratch: (max_rows / kAttnBQ + B + 1) x int4 work list of the prefill kernel, 16-byte aligned
     int32_t* n_items;          // scratch [1]
 };
 constexpr int kAttnBQ = 128;   // executed rows per prefill-attention workgroup
