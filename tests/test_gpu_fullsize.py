@@ -25,7 +25,7 @@ def qt():
     return pkg
 
 
-def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed):
+def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed, threshold=None):
     T = B * S
     tensors = si.layer_tensors(shape, 0, seed, unit_gains=True)
     x = si.hidden_states(shape, T, seed)
@@ -33,7 +33,10 @@ def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed):
     cfg = qt.cfg_from_shape(shape)
     lw = qt.quantize_layer(tensors, shape.bits, shape.group)
     ctx = qt.Context()
-    qt.qtale_set_exec_ratio(ctx, ratio)
+    if threshold is None:
+        qt.qtale_set_exec_ratio(ctx, ratio)
+    else:
+        qt.qtale_set_threshold(ctx, threshold)                   # count known on the device only: persistent GEMM form
     xg = x.cuda()
     idx = torch.full((T,), -1, dtype=torch.int32, device="cuda")
     cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -43,9 +46,11 @@ def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed):
     # selection over the whole call
     z_ref = orc.router_scores(to_f64(x), tensors["router_w"].numpy(), 0.0)
     assert np.array_equal(z.cpu().numpy().view(np.uint32), z_ref.view(np.uint32))
-    want_idx = orc.select_ratio(z_ref, ratio)
+    want_idx = orc.select_ratio(z_ref, ratio) if threshold is None else orc.select_threshold(z_ref, threshold)
     k = int(cnt.item())
-    assert k == len(want_idx) == orc.executed_count(ratio, T)
+    assert k == len(want_idx)
+    if threshold is None:
+        assert k == orc.executed_count(ratio, T)
     got_idx = idx[:k].cpu().numpy()
     assert np.array_equal(got_idx, want_idx)
     # bypassed rows untouched everywhere
@@ -63,12 +68,23 @@ def _prefill_case(qt, shape, B, S, ratio, seq_to_check, seed):
     assert err <= TOL, err
     # codes of the largest matrix
     codes = q["down"][0]
-    assert np.array_equal(lw.lin["down"].codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes))
+    assert np.array_equal(lw.lin["down"].codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes, shape.bits))
     return err
 
 
 def test_llama7b_shaped_prefill_layer_8x1024_bf16_ratio_half(qt):
     _prefill_case(qt, si.C2, 8, 1024, 0.5, seq_to_check=3, seed=11)
+
+
+def test_llama7b_shaped_prefill_layer_threshold_mode(qt):
+    # Eq. 9 verbatim at full size: about 62 % of the 8192 tokens execute at theta = 0.4 with these scores; the
+    # GEMMs walk the live tiles with persistent workgroups (more tiles than resident workgroups)
+    _prefill_case(qt, si.C2, 8, 1024, None, seq_to_check=5, seed=14, threshold=0.4)
+
+
+def test_llama7b_shaped_prefill_layer_three_bit(qt):
+    import dataclasses
+    _prefill_case(qt, dataclasses.replace(si.C2, bits=3), 8, 1024, 0.5, seq_to_check=2, seed=15)
 
 
 def test_llama3_8b_shaped_gqa_prefill_layer_4x4096_ratio_06(qt):

@@ -119,6 +119,13 @@ def test_layer_with_two_output_mlp_router(qt, mode, val):
     assert orc.parity_error(to_f64(got)[widx], want[widx]) <= TOL
 
 
+def test_threshold_mode_with_more_tiles_than_resident_workgroups(qt):
+    # 12800 rows x (2 x 688) gate/up columns = 600 tiles of 128 x 256: every persistent workgroup walks several
+    # tiles; theta = 0.35 keeps most rows, so the live tile count is only known on the device
+    shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "bf16")
+    _check_layer(qt, shape, 12800, [1280] * 10, "threshold", 0.35, seed=24, std=0.08)
+
+
 def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     T = sum(lens)
     B = len(lens)
