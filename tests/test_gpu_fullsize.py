@@ -133,3 +133,58 @@ def test_llama7b_shaped_decode_step_batch64_ctx2048(qt):
         gv = to_f64(kv.v.cpu()[sub, ctx_len])
         assert orc.parity_error(gk, okv.k[:, ctx_len]) <= TOL
         assert orc.parity_error(gv, okv.v[:, ctx_len]) <= TOL
+
+
+C5 = si.LayerShape(5120, 40, 40, 128, 13824, 4, 128, "bf16")     # LLaMA-13B-shaped layer
+
+
+@pytest.mark.parametrize("bits,ratio", [(4, 0.3), (3, 1.0)])
+def test_llama13b_shaped_prefill_layer_16x512(qt, bits, ratio):
+    import dataclasses
+    _prefill_case(qt, dataclasses.replace(C5, bits=bits), 16, 512, ratio, seq_to_check=9, seed=16 + bits)
+
+
+def test_llama13b_shaped_decode_step_batch128_ctx4096(qt):
+    # decode after the prefill: 128 one-token sequences against 4096 cached entries each; ratio 1.0 runs the
+    # matrix-core GEMM with a single 128-row tile, ratio 0.3 (38 rows) the skinny kernel
+    shape = si.LayerShape(5120, 40, 40, 128, 13824, 4, 128, "fp16")
+    B, ctx_len, cap, seed = 128, 4096, 4096 + 8, 18
+    W = shape.n_kv_heads * shape.head_dim
+    tensors = si.layer_tensors(shape, 0, seed, unit_gains=True)
+    x = si.hidden_states(shape, B, seed)
+    offs, pos = si.ragged_sequences([1] * B, starts=[ctx_len] * B)
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    kc = torch.randn(B, cap, W, device="cuda", dtype=torch.float16, generator=g)      # 5.4 GB each
+    vc = torch.randn(B, cap, W, device="cuda", dtype=torch.float16, generator=g)
+    cfg = qt.cfg_from_shape(shape)
+    lw = qt.quantize_layer(tensors, shape.bits, shape.group)
+    p, _ = oracle_layer(shape, 0, seed, tensors=tensors)
+    z_ref = orc.router_scores(to_f64(x), tensors["router_w"].numpy(), 0.0)
+    ctx = qt.Context()
+    for ratio in (1.0, 0.3):
+        qt.qtale_set_exec_ratio(ctx, ratio)
+        kv = qt.KVCache(kc, vc, torch.full((B,), ctx_len, dtype=torch.int32).cuda())
+        xg = x.cuda()
+        idx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        qt.qtale_layer_forward(ctx, cfg, lw, xg, offs.cuda(), pos.cuda(), kv=kv, sel_idx=idx, sel_count=cnt)
+        torch.cuda.synchronize()
+        want_idx = orc.select_ratio(z_ref, ratio)
+        k = int(cnt.item())
+        assert k == len(want_idx) == orc.executed_count(ratio, B)
+        assert np.array_equal(idx[:k].cpu().numpy(), want_idx)
+        got = xg.cpu()
+        skipped = np.setdiff1d(np.arange(B), want_idx)
+        assert torch.equal(got[skipped], x[skipped])
+        executed = np.isin(np.arange(B), want_idx)
+        assert np.array_equal(kv.kv_len.cpu().numpy(), ctx_len + executed.astype(np.int32))
+        sub = [int(t) for t in want_idx[[0, len(want_idx) // 2, -1]]]
+        kc_sub, vc_sub = kc[sub, :ctx_len + 1].cpu(), vc[sub, :ctx_len + 1].cpu()
+        okv = orc.KVCache(to_f64(kc_sub), to_f64(vc_sub), [ctx_len] * len(sub))
+        o_s, p_s = si.ragged_sequences([1] * len(sub), starts=[ctx_len] * len(sub))
+        want, _, _ = orc.layer_forward(to_f64(x[sub]), p, cfg_dict(shape), o_s.numpy(), p_s.numpy(), "forced",
+                                       list(range(len(sub))), okv)
+        assert orc.parity_error(to_f64(got[sub]), want) <= TOL
+        assert orc.parity_error(to_f64(kv.k[sub, ctx_len].cpu()), okv.k[:, ctx_len]) <= TOL
+        # the rows appended at index ctx_len lie beyond the length the next ratio starts from: no restore needed
+
