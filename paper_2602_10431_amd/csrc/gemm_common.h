@@ -14,6 +14,7 @@ struct GemmDev {
     const uint32_t* sz[3];
     int N[3], NF[3], npad[3], colbase[3];
     int n_w, vf_total, tiles_m, tiles_n;
+    int row_chunks;                // skinny kernel: 64-row chunks of the activation matrix (1 for M <= 64)
     void* out;
     int ldo;
     const void* resid;

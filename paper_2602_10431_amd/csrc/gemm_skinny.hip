@@ -34,13 +34,19 @@ gemm_skinny_kernel(GemmDev p) {
     __shared__ __attribute__((aligned(16))) char smem[kSlabBytes > kStageBytes ? kSlabBytes : kStageBytes];
     float* slab = reinterpret_cast<float*>(smem);
 
-    const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
+    // Workgroup id -> (column tile, 64-row chunk).  With more than 64 rows the weights are streamed once per
+    // chunk; ids are dealt round-robin to the 8 XCDs, so the chunks of one column tile are given ids 8 apart:
+    // they run on the same XCD right after each other and the second one finds the weights in that L2.
+    const int within = blockIdx.x % (8 * p.row_chunks);
+    const int tile_n = (blockIdx.x / (8 * p.row_chunks)) * 8 + (within & 7);
+    const int row0 = (within >> 3) * 64;
+    if (tile_n >= p.tiles_n) return;
+    const int M = min((p.count ? min(*p.count, p.M_max) : p.M_max) - row0, ROWS);
     if (M <= 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     const uint32_t magic = dequant_magic();
-    const int tile_n = blockIdx.x;
 
     const char* bbase[NFB];
     const uint32_t* sbase[NFB];
@@ -98,7 +104,7 @@ gemm_skinny_kernel(GemmDev p) {
         }
     };
     auto fetch_a = [&](int kt, u32x4_t* ar) {
-        const half_t* base = p.A + kt * 64;
+        const half_t* base = p.A + static_cast<size_t>(row0) * p.K + kt * 64;
         uint32_t shift = 0;
         if (RAGGED) {                               // chunks starting at or beyond K read the row's last
             const int col = kt * 64 + (lane & 7) * 8;           // valid chunk: the weights there are 0
@@ -183,12 +189,13 @@ gemm_skinny_kernel(GemmDev p) {
     // slab column of the lane's first value (SwiGLU: gate fragment 2*fo, up fragment 2*fo+1)
     const int sc = EPI == EPI_SWIGLU_F16 ? (2 * fo) * 32 + (c4 & 31) : c4;
 
-    for (int row = tid / LPR; row < ROWS; row += RPP) {
-        if (!col_ok || row >= M) continue;
+    for (int lrow = tid / LPR; lrow < ROWS; lrow += RPP) {
+        if (!col_ok || lrow >= M) continue;
+        const int row = row0 + lrow;                 // row of the whole activation / output matrix
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f), u = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float* s = slab + w * (ROWS * CSTR) + row * CSTR + sc;
+            const float* s = slab + w * (ROWS * CSTR) + lrow * CSTR + sc;
             const float4 t = *reinterpret_cast<const float4*>(s);
             v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
             if (EPI == EPI_SWIGLU_F16) {
@@ -226,8 +233,10 @@ gemm_skinny_kernel(GemmDev p) {
 
 template <int BITS, int NFB, int NW, int MF, int GPT, int EPI>
 static hipError_t launch_one(GemmDev& d, hipStream_t stream) {
-    const int blocks = (d.vf_total + NFB - 1) / NFB;
-    if (blocks == 0) return hipSuccess;
+    d.tiles_n = (d.vf_total + NFB - 1) / NFB;
+    if (d.tiles_n == 0) return hipSuccess;
+    d.row_chunks = (d.M_max + 63) / 64;
+    const int blocks = ((d.tiles_n + 7) / 8) * 8 * d.row_chunks;
     if (d.K % 64 != 0)
         hipLaunchKernelGGL((gemm_skinny_kernel<BITS, NFB, NW, MF, GPT, EPI, true>), dim3(blocks), dim3(NW * 64), 0, stream, d);
     else

@@ -398,7 +398,11 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     d.idx = a.idx;
     d.bf16 = a.bf16;
     d.bits = a.bits;
-    if (d.M_max <= 64) return launch_gemm_skinny(d, a.epilogue, stream);
+    // Few rows: the weight stream dominates and 128-row tiles cannot fill the chip (a 5120-column output is 20
+    // workgroups).  Up to 64 rows the skinny kernel streams the weights once; up to 256 rows it runs one 64-row
+    // chunk per workgroup (measured on 13B-shaped linears at 128 rows: 26-59 us against 64-178 us here; at 256
+    // rows the two are level).
+    if (d.M_max <= 256) return launch_gemm_skinny(d, a.epilogue, stream);
     if (a.bits == 3) {
         if (a.group == 32) return launch_gpt<3, 2>(d, a.epilogue, stream);
         return launch_gpt<3, 1>(d, a.epilogue, stream);

@@ -50,7 +50,8 @@ def test_quantize_rejects_bad_parameters(qt):
 
 
 @pytest.mark.parametrize("M,N,K,G", [(64, 256, 256, 32), (32, 256, 688, 32), (7, 688, 256, 32), (300, 416, 512, 128),
-                                     (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128)])
+                                     (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128),
+                                     (65, 4096, 1024, 128), (130, 416, 688, 32), (256, 1024, 512, 64)])
 @pytest.mark.parametrize("bits", [4, 3])
 def test_linear_w4a16_matches_oracle(qt, M, N, K, G, bits):
     W = _w(N, K, M + N + K)
