@@ -215,7 +215,7 @@ def main():
                     help="also run a plain 256 MiB device copy (calibrates FETCH_SIZE/WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU only: this build uses no second GPU (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU only: the library runs on a single GPU (run with --gpus 1)")
 
     import torch
     import paper_2602_10431_amd as qt
