@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-int3", action="store_true")
+    ap.add_argument("--decode-only", type=float, default=None, metavar="RATIO",
+                    help="profiling aid: run only the decode section at this execution ratio and print its JSON")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates FETCH_SIZE/WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -239,6 +241,9 @@ def main():
         layers.append(qt.quantize_layer(t, shape.bits, shape.group, keep_canonical=False))
         del t
     torch.cuda.synchronize()
+    if args.decode_only is not None:
+        print(json.dumps({"decode": decode_section(qt, si, torch, layers, L, ratios=(args.decode_only,))}))
+        return
     stack = qt.Stack(cfg, layers)
     offs, pos = si.equal_sequences(B, S)
     offs, pos = offs.to(dev), pos.to(dev)
