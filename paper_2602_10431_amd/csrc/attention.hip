@@ -311,9 +311,10 @@ attn_decode_kernel(AttnDev p) {
     constexpr int LPK = D / 8;            // lanes per key (each lane owns 8 of the D columns)
     constexpr int KPW = 64 / LPK;         // keys per wave per step
     constexpr int UNR = 4;
-    const int i = blockIdx.x;
+    // kv head fastest: neighbouring workgroups stream neighbouring 2*D-byte pieces of the same cached token rows
+    const int i = blockIdx.y;
     if (i >= *p.count) return;
-    const int hk = blockIdx.y;
+    const int hk = blockIdx.x;
     const int b = p.row_seq[i];
     const int row_begin = p.cu_exec[b];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -351,18 +352,31 @@ attn_decode_kernel(AttnDev p) {
     }
 
     const int step = 4 * KPW;             // keys per workgroup step
+    // The keys and values of the next step are requested before the current step is consumed, so the memory
+    // pipe never drains while the lanes do their dot products and exponentials (keys past the end are clamped
+    // to the last one and masked).
+    half8_t kn[UNR], vn[UNR];
+    auto fetch = [&](int kb) {
+        const int k0 = kb + wave * KPW + slot;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int kc = min(k0 + u * step, n_keys - 1);
+            kn[u] = *reinterpret_cast<const half8_t*>(kbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
+            vn[u] = *reinterpret_cast<const half8_t*>(vbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
+        }
+    };
+    fetch(0);
     for (int kb = 0; kb < n_keys; kb += UNR * step) {          // trip count is uniform over the workgroup
         const int k0 = kb + wave * KPW + slot;
         half8_t kv[UNR], vv[UNR];
         bool ok[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int key = k0 + u * step;
-            ok[u] = key < n_keys;
-            const int kc = ok[u] ? key : n_keys - 1;
-            kv[u] = *reinterpret_cast<const half8_t*>(kbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
-            vv[u] = *reinterpret_cast<const half8_t*>(vbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
+            ok[u] = k0 + u * step < n_keys;
+            kv[u] = kn[u];
+            vv[u] = vn[u];
         }
+        fetch(min(kb + UNR * step, n_keys - 1));               // past the end: one redundant, unused fetch
 #pragma unroll
         for (int r = 0; r < REP; ++r) {
             float s[UNR];
@@ -436,7 +450,7 @@ attn_decode_kernel(AttnDev p) {
 
 template <int D>
 static hipError_t launch_decode_d(const AttnDev& d, int rep, int rows, int nkv, hipStream_t stream) {
-    const dim3 grid(rows, nkv), block(256);
+    const dim3 grid(nkv, rows), block(256);
     switch (rep) {
         case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, block, 0, stream, d); break;
         case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, block, 0, stream, d); break;
