@@ -88,8 +88,8 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=
     cap = ctx_len + steps + 8
     kvs = []
     for l in range(L):
-        k = torch.randn(B, cap, 4096, device=dev, dtype=torch.float16)
-        v = torch.randn(B, cap, 4096, device=dev, dtype=torch.float16)
+        k = torch.randn(B, 32, cap, 128, device=dev, dtype=torch.float16)      # [B][kv heads][cap][head_dim]
+        v = torch.randn(B, 32, cap, 128, device=dev, dtype=torch.float16)
         kvs.append(qt.KVCache(k, v, torch.full((B,), ctx_len, dtype=torch.int32, device=dev)))
     stack = qt.Stack(cfg, fp16_layers, kvs)
     offs = torch.arange(0, B + 1, dtype=torch.int32, device=dev)

@@ -124,7 +124,8 @@ typedef struct {
 } qtale_layer_weights;
 
 /* Per-layer K/V cache holding entries of EXECUTED tokens only (a bypassed token produces no key or
- * value at that layer).  k_cache/v_cache: [B][cap][n_kv_heads*head_dim] fp16; kv_len [B] int32 device:
+ * value at that layer).  k_cache/v_cache: [B][n_kv_heads][cap][head_dim] fp16 (the entries of one sequence
+ * and head are contiguous: decode attention streams them at the full memory rate); kv_len [B] int32 device:
  * entries already present per sequence.  A forward call appends the executed tokens of sequence b (keys
  * after rotary embedding) at kv_len[b].. and adds their number to kv_len[b].  The caller guarantees
  * kv_len[b] + (tokens of sequence b in the call) <= cap; rows that would not fit are dropped. */

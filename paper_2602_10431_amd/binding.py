@@ -238,9 +238,27 @@ class LayerWeights:
 
 class KVCache:
     def __init__(self, k_cache, v_cache, kv_len):
+        # k_cache / v_cache: [B, n_kv_heads, cap, head_dim] fp16, contiguous
         assert k_cache.dtype == torch.float16 and v_cache.dtype == torch.float16 and kv_len.dtype == torch.int32
+        assert k_cache.dim() == 4 and k_cache.shape == v_cache.shape and k_cache.is_contiguous() and v_cache.is_contiguous()
         self.k, self.v, self.kv_len = k_cache, v_cache, kv_len
-        self.cap = k_cache.shape[1]
+        self.cap = k_cache.shape[2]
+
+    @classmethod
+    def from_token_major(cls, k, v, kv_len, n_kv_heads):
+        """k, v: [B, cap, n_kv_heads * head_dim] (one row per cached token) -> the library's layout."""
+        B, cap, W = k.shape
+        d = W // n_kv_heads
+        conv = lambda t: t.view(B, cap, n_kv_heads, d).permute(0, 2, 1, 3).contiguous()
+        return cls(conv(k), conv(v), kv_len)
+
+    def k_token_major(self):
+        B, nkv, cap, d = self.k.shape
+        return self.k.permute(0, 2, 1, 3).reshape(B, cap, nkv * d)
+
+    def v_token_major(self):
+        B, nkv, cap, d = self.v.shape
+        return self.v.permute(0, 2, 1, 3).reshape(B, cap, nkv * d)
 
     def c_struct(self):
         return qtale_kv(self.k.data_ptr(), self.v.data_ptr(), self.kv_len.data_ptr(), self.cap)

@@ -76,9 +76,9 @@ flash_prefill_kernel(AttnDev p) {
     int kv_stride, base_len;
     if (p.k_cache) {
         base_len = p.kv_old[b];
-        kv_stride = p.nkv * D;
-        kbase = p.k_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
-        vbase = p.v_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+        kv_stride = D;                                           // cache [B][n_kv_heads][cap][D]: a head's entries are contiguous
+        kbase = p.k_cache + (static_cast<size_t>(b) * p.nkv + hk) * p.cap * D;
+        vbase = p.v_cache + (static_cast<size_t>(b) * p.nkv + hk) * p.cap * D;
     } else {
         base_len = 0;
         kv_stride = p.width;
@@ -311,7 +311,7 @@ attn_decode_kernel(AttnDev p) {
     constexpr int LPK = D / 8;            // lanes per key (each lane owns 8 of the D columns)
     constexpr int KPW = 64 / LPK;         // keys per wave per step
     constexpr int UNR = 4;
-    // kv head fastest: neighbouring workgroups stream neighbouring 2*D-byte pieces of the same cached token rows
+    // kv head fastest: the workgroups of one executed row are launched together
     const int i = blockIdx.y;
     if (i >= *p.count) return;
     const int hk = blockIdx.x;
@@ -324,9 +324,9 @@ attn_decode_kernel(AttnDev p) {
     const half_t* vbase;
     int kv_stride, n_keys;
     if (p.k_cache) {
-        kv_stride = p.nkv * D;
-        kbase = p.k_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
-        vbase = p.v_cache + static_cast<size_t>(b) * p.cap * kv_stride + hk * D;
+        kv_stride = D;                        // cache [B][n_kv_heads][cap][D]: one contiguous stream per workgroup
+        kbase = p.k_cache + (static_cast<size_t>(b) * p.nkv + hk) * p.cap * D;
+        vbase = p.v_cache + (static_cast<size_t>(b) * p.nkv + hk) * p.cap * D;
         n_keys = min(p.kv_old[b] + (i - row_begin) + 1, p.cap);
     } else {
         kv_stride = p.width;

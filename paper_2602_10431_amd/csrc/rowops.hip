@@ -155,7 +155,7 @@ hipError_t launch_rmsnorm_f32(const float* h, int H, const int32_t* count, int m
 // a layer).  One workgroup per executed row: the d/2 (cos, sin) pairs of the row's position are
 // evaluated once in fp64 into LDS, then every thread rotates 8 pairs of one q or k head with 16-byte
 // accesses.  With a cache, rotated k and v are also appended at kv_old[seq] + (rank of the row inside
-// its sequence).
+// its sequence), one head_dim-wide piece per kv head.
 __global__ void __launch_bounds__(256)
 rope_append_kernel(RopeArgs a) {
     __shared__ float cs[64], sn[64];              // head_dim <= 128
@@ -165,13 +165,15 @@ rope_append_kernel(RopeArgs a) {
     const int d = a.d, half = d >> 1;
     const int width = (a.nh + 2 * a.nkv) * d;
     half_t* row = reinterpret_cast<half_t*>(a.qkv) + static_cast<size_t>(i) * width;
-    half_t* kdst = nullptr;
+    // cache layout [B][n_kv_heads][cap][d]: entry (b, head, slot) starts at ((b * nkv + head) * cap + slot) * d
+    half_t* kdst = nullptr;                       // entry (b, head 0, slot); heads are head_step halves apart
     half_t* vdst = nullptr;
+    const size_t head_step = static_cast<size_t>(a.cap) * d;
     if (a.k_cache) {
         const int b = a.row_seq[i];
         const int slot = a.kv_old[b] + (i - a.cu_exec[b]);
         if (slot < a.cap) {
-            const size_t off = (static_cast<size_t>(b) * a.cap + slot) * (static_cast<size_t>(a.nkv) * d);
+            const size_t off = (static_cast<size_t>(b) * a.nkv * a.cap + slot) * d;
             kdst = reinterpret_cast<half_t*>(a.k_cache) + off;
             vdst = reinterpret_cast<half_t*>(a.v_cache) + off;
         }
@@ -203,13 +205,15 @@ rope_append_kernel(RopeArgs a) {
         *reinterpret_cast<half8_t*>(hp + p0) = rlo;
         *reinterpret_cast<half8_t*>(hp + p0 + half) = rhi;
         if (kdst && hd >= a.nh) {
-            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * d + p0) = rlo;
-            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * d + p0 + half) = rhi;
+            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * head_step + p0) = rlo;
+            *reinterpret_cast<half8_t*>(kdst + (hd - a.nh) * head_step + p0 + half) = rhi;
         }
     }
     if (vdst) {
         const half8_t* vsrc = reinterpret_cast<const half8_t*>(row + static_cast<size_t>(a.nh + a.nkv) * d);
-        for (int e = threadIdx.x; e < (a.nkv * d) >> 3; e += blockDim.x) reinterpret_cast<half8_t*>(vdst)[e] = vsrc[e];
+        const int cpr = d >> 3;                    // 16-byte chunks per head
+        for (int e = threadIdx.x; e < a.nkv * cpr; e += blockDim.x)
+            *reinterpret_cast<half8_t*>(vdst + (e / cpr) * head_step + (e % cpr) * 8) = vsrc[e];
     }
 }
 

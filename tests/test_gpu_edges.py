@@ -101,7 +101,7 @@ def test_first_decode_step_on_empty_caches(qt, layer):
     x = si.hidden_states(SHAPE, B, 52)
     offs, pos = si.ragged_sequences([1] * B, starts=[0] * B)
     kc, vc = si.kv_cache(SHAPE, B, cap, 0, 52)
-    kv = qt.KVCache(kc.cuda(), vc.cuda(), torch.zeros(B, dtype=torch.int32).cuda())
+    kv = qt.KVCache.from_token_major(kc.cuda(), vc.cuda(), torch.zeros(B, dtype=torch.int32).cuda(), SHAPE.n_kv_heads)
     got, idx, k = _run(qt, lw, x, offs, pos, "ratio", 0.6, kv=kv)
     okv = orc.KVCache(to_f64(kc), to_f64(vc), [0] * B)
     want, widx, _ = orc.layer_forward(to_f64(x), p, cfg_dict(SHAPE), offs.numpy(), pos.numpy(), "ratio", 0.6, okv)
@@ -117,7 +117,7 @@ def test_cache_exactly_full_after_the_call(qt, layer):
     x = si.hidden_states(SHAPE, 6, 53)
     offs, pos = si.ragged_sequences(lens, starts=old)
     kc, vc = si.kv_cache(SHAPE, 2, cap, 0, 53)
-    kv = qt.KVCache(kc.cuda(), vc.cuda(), torch.tensor(old, dtype=torch.int32).cuda())
+    kv = qt.KVCache.from_token_major(kc.cuda(), vc.cuda(), torch.tensor(old, dtype=torch.int32).cuda(), SHAPE.n_kv_heads)
     got, idx, k = _run(qt, lw, x, offs, pos, "ratio", 1.0, kv=kv)
     okv = orc.KVCache(to_f64(kc), to_f64(vc), old)
     want, widx, _ = orc.layer_forward(to_f64(x), p, cfg_dict(SHAPE), offs.numpy(), pos.numpy(), "ratio", 1.0, okv)

@@ -106,7 +106,7 @@ def test_llama7b_shaped_decode_step_batch64_ctx2048(qt):
     check = [0, 17, 40, 63]
     for ratio, k_want in [(1.0, 64), (0.8, 51), (0.6, 38), (0.4, 26)]:
         qt.qtale_set_exec_ratio(ctx, ratio)                      # runtime change, weights untouched
-        kv = qt.KVCache(kc.cuda(), vc.cuda(), torch.full((B,), ctx_len, dtype=torch.int32).cuda())
+        kv = qt.KVCache.from_token_major(kc.cuda(), vc.cuda(), torch.full((B,), ctx_len, dtype=torch.int32).cuda(), shape.n_kv_heads)
         xg = x.cuda()
         idx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
         cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -129,8 +129,8 @@ def test_llama7b_shaped_decode_step_batch64_ctx2048(qt):
         want, _, _ = orc.layer_forward(to_f64(x[sub]), p, cfg_dict(shape), o_s.numpy(), p_s.numpy(), "forced",
                                        list(range(len(sub))), okv)
         assert orc.parity_error(to_f64(got[sub]), want) <= TOL
-        gk = to_f64(kv.k.cpu()[sub, ctx_len])
-        gv = to_f64(kv.v.cpu()[sub, ctx_len])
+        gk = to_f64(kv.k[sub, :, ctx_len].reshape(len(sub), -1).cpu())
+        gv = to_f64(kv.v[sub, :, ctx_len].reshape(len(sub), -1).cpu())
         assert orc.parity_error(gk, okv.k[:, ctx_len]) <= TOL
         assert orc.parity_error(gv, okv.v[:, ctx_len]) <= TOL
 
@@ -149,13 +149,12 @@ def test_llama13b_shaped_decode_step_batch128_ctx4096(qt):
     # matrix-core GEMM with a single 128-row tile, ratio 0.3 (38 rows) the skinny kernel
     shape = si.LayerShape(5120, 40, 40, 128, 13824, 4, 128, "fp16")
     B, ctx_len, cap, seed = 128, 4096, 4096 + 8, 18
-    W = shape.n_kv_heads * shape.head_dim
     tensors = si.layer_tensors(shape, 0, seed, unit_gains=True)
     x = si.hidden_states(shape, B, seed)
     offs, pos = si.ragged_sequences([1] * B, starts=[ctx_len] * B)
     g = torch.Generator(device="cuda").manual_seed(seed)
-    kc = torch.randn(B, cap, W, device="cuda", dtype=torch.float16, generator=g)      # 5.4 GB each
-    vc = torch.randn(B, cap, W, device="cuda", dtype=torch.float16, generator=g)
+    kc = torch.randn(B, shape.n_kv_heads, cap, shape.head_dim, device="cuda", dtype=torch.float16, generator=g)   # 5.4 GB each,
+    vc = torch.randn(B, shape.n_kv_heads, cap, shape.head_dim, device="cuda", dtype=torch.float16, generator=g)   # library layout
     cfg = qt.cfg_from_shape(shape)
     lw = qt.quantize_layer(tensors, shape.bits, shape.group)
     p, _ = oracle_layer(shape, 0, seed, tensors=tensors)
@@ -179,12 +178,13 @@ def test_llama13b_shaped_decode_step_batch128_ctx4096(qt):
         executed = np.isin(np.arange(B), want_idx)
         assert np.array_equal(kv.kv_len.cpu().numpy(), ctx_len + executed.astype(np.int32))
         sub = [int(t) for t in want_idx[[0, len(want_idx) // 2, -1]]]
-        kc_sub, vc_sub = kc[sub, :ctx_len + 1].cpu(), vc[sub, :ctx_len + 1].cpu()
+        tok = lambda t: t[sub, :, :ctx_len + 1].permute(0, 2, 1, 3).reshape(len(sub), ctx_len + 1, -1).cpu()   # one row per token
+        kc_sub, vc_sub = tok(kc), tok(vc)
         okv = orc.KVCache(to_f64(kc_sub), to_f64(vc_sub), [ctx_len] * len(sub))
         o_s, p_s = si.ragged_sequences([1] * len(sub), starts=[ctx_len] * len(sub))
         want, _, _ = orc.layer_forward(to_f64(x[sub]), p, cfg_dict(shape), o_s.numpy(), p_s.numpy(), "forced",
                                        list(range(len(sub))), okv)
         assert orc.parity_error(to_f64(got[sub]), want) <= TOL
-        assert orc.parity_error(to_f64(kv.k[sub, ctx_len].cpu()), okv.k[:, ctx_len]) <= TOL
+        assert orc.parity_error(to_f64(kv.k[sub, :, ctx_len].reshape(len(sub), -1).cpu()), okv.k[:, ctx_len]) <= TOL
         # the rows appended at index ctx_len lie beyond the length the next ratio starts from: no restore needed
 

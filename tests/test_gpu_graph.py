@@ -22,7 +22,8 @@ def _decode_setup(qt, shape, L, B, cap, seed, old_lens):
     caches = [si.kv_cache(shape, B, cap, l, seed) for l in range(L)]
 
     def fresh_stack():
-        kvs = [qt.KVCache(k.cuda(), v.cuda(), torch.tensor(old_lens, dtype=torch.int32).cuda()) for k, v in caches]
+        kvs = [qt.KVCache.from_token_major(k.cuda(), v.cuda(), torch.tensor(old_lens, dtype=torch.int32).cuda(), shape.n_kv_heads)
+               for k, v in caches]
         return qt.Stack(qt.cfg_from_shape(shape), layers, kvs), kvs
 
     return fresh_stack

@@ -133,7 +133,7 @@ def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     x = si.hidden_states(shape, T, seed)
     offs, pos = si.ragged_sequences(lens, starts)
     kc, vc = si.kv_cache(shape, B, cap, 0, seed)
-    kv = qt.KVCache(kc.cuda(), vc.cuda(), torch.tensor(old_lens, dtype=torch.int32).cuda())
+    kv = qt.KVCache.from_token_major(kc.cuda(), vc.cuda(), torch.tensor(old_lens, dtype=torch.int32).cuda(), shape.n_kv_heads)
     got, idx, _ = _run_layer(qt, shape, tensors, x, offs, pos, "ratio", ratio, kv=kv)
     p, _ = oracle_layer(shape, 0, seed, tensors=tensors)
     okv = orc.KVCache(to_f64(kc), to_f64(vc), old_lens)
@@ -141,7 +141,7 @@ def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     assert np.array_equal(idx, widx)
     assert orc.parity_error(to_f64(got)[widx], want[widx]) <= TOL
     assert np.array_equal(kv.kv_len.cpu().numpy(), okv.kv_len)
-    gk, gv = to_f64(kv.k.cpu()), to_f64(kv.v.cpu())
+    gk, gv = to_f64(kv.k_token_major().cpu()), to_f64(kv.v_token_major().cpu())
     for b in range(B):
         n0, n1 = old_lens[b], int(okv.kv_len[b])
         assert np.array_equal(gk[b, :n0], okv.k[b, :n0])         # old entries untouched
