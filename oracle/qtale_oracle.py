@@ -14,7 +14,8 @@ What is implemented, and the passage of the paper each part follows:
                                                                     (Sec. 3.4, Eq. 9)
 * active tokens are gathered into a dense matrix before the layer   (App. B.2)
 * weight-only group quantization with groups along the input dimension,
-  4 bit and 3 bit                                                   (Sec. 4.1 setup)
+  4 bit and 3 bit (Sec. 4.1 setup); 2 bit for the mixed 2-/4-bit stack of the
+  paper's mixed-precision appendix
 * two-phase grid search for the global theta (coarse 0.05, fine 0.01 on (0, 0.5]),
   with the average execution ratio as the objective                 (Sec. 3.4)
 
@@ -98,6 +99,7 @@ def pack_codes(codes, bits=4):
 
     4 bit: ceil(K/8) words per row, nibble j of word w holds the code of k = 8*w + j
     (least-significant nibble first); rows are padded with code 0.
+    2 bit: ceil(K/16) words per row, bit pair j of word w holds the code of k = 16*w + j.
     3 bit: the codes of a row form one little-endian bit stream, code k at bits [3k, 3k+3), cut into
     32-bit words (32 codes fill exactly 3 words); rows are padded with code 0 to a whole number of
     32-code blocks, i.e. 3*ceil(K/32) words per row."""
@@ -109,6 +111,14 @@ def pack_codes(codes, bits=4):
         out = np.zeros((N, nw), dtype=np.uint32)
         for j in range(8):
             out |= padded[:, j::8] << np.uint32(4 * j)
+        return out
+    if bits == 2:
+        nw = (K + 15) // 16
+        padded = np.zeros((N, nw * 16), dtype=np.uint32)
+        padded[:, :K] = codes
+        out = np.zeros((N, nw), dtype=np.uint32)
+        for j in range(16):
+            out |= padded[:, j::16] << np.uint32(2 * j)
         return out
     assert bits == 3
     nb = (K + 31) // 32
@@ -138,6 +148,11 @@ def unpack_codes(words, K, bits=4):
         out = np.zeros((N, nw * 8), dtype=np.uint8)
         for j in range(8):
             out[:, j::8] = (words >> np.uint32(4 * j)) & np.uint32(0xF)
+        return out[:, :K]
+    if bits == 2:
+        out = np.zeros((N, nw * 16), dtype=np.uint8)
+        for j in range(16):
+            out[:, j::16] = (words >> np.uint32(2 * j)) & np.uint32(0x3)
         return out[:, :K]
     assert bits == 3 and nw % 3 == 0
     out = np.zeros((N, (nw // 3) * 32), dtype=np.uint8)

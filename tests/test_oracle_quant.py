@@ -15,7 +15,7 @@ def _rand_w(N, K, seed, std=0.02):
     return (rng.standard_normal((N, K)) * std).astype(np.float32)
 
 
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2])
 @pytest.mark.parametrize("N,K,G", [(8, 128, 128), (5, 688, 32), (7, 256, 32), (3, 40, 16), (4, 130, 128)])
 def test_codes_are_the_nearest_representable_value(N, K, G, bits):
     W = _rand_w(N, K, seed=N * 1000 + K)
@@ -141,6 +141,26 @@ def test_three_bit_lattice_and_one_sided_groups():
     assert np.all(z == 0) and codes.max() == 7
     codes, s, z = orc.quantize_rtn(-Wp, 3, 32)
     assert np.all(z == 7) and codes.min() == 0
+
+
+def test_two_bit_pack_hand_written_words():
+    codes = np.array([[3, 0, 1, 2] + [0] * 11 + [3, 2, 1]], dtype=np.uint8)       # K = 18: two words
+    words = orc.pack_codes(codes, 2)
+    assert words.dtype == np.uint32 and words.shape == (1, 2)
+    assert words[0, 0] == (3 | (1 << 4) | (2 << 6) | (3 << 30))
+    assert words[0, 1] == (2 | (1 << 2))
+    assert np.array_equal(orc.unpack_codes(words, 18, 2), codes)
+    rng = np.random.default_rng(8)
+    codes = rng.integers(0, 4, size=(4, 688)).astype(np.uint8)
+    assert np.array_equal(orc.unpack_codes(orc.pack_codes(codes, 2), 688, 2), codes)
+
+
+def test_two_bit_lattice():
+    s0 = float(np.float16(0.07))
+    j = np.array([[0, 3, 1, 2, 2, 1, 3, 0]] * 2)
+    W = ((j - 1) * s0).astype(np.float32)
+    codes, s, z = orc.quantize_rtn(W, 2, 8)
+    assert np.all(z == 1) and np.all(codes == j)
 
 
 def test_pack_roundtrip_ragged():
