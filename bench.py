@@ -154,7 +154,7 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=
             "hbm_peak_GBps": HBM_PEAK_GBS, "by_exec_ratio": res}
 
 
-def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode):
+def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode, layers4=None):
     """The 3-bit variant of the same workload (Sec. 4.1 evaluates 4-bit and 3-bit weights): prefill step
     and gate/up GEMM rate, then two decode ratios."""
     import dataclasses
@@ -192,6 +192,25 @@ def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode):
     out = {"workload": "same stack and batch with 3-bit group-128 codes (0.375 B/weight)",
            "prefill_tokens_per_s": T / dt, "prefill_ms_per_step": dt * 1e3,
            "gate_up_gemm_ms": gu_ms, "gate_up_gemm_TFLOPs": 2.0 * k_exec * 2 * shape.inter * shape.hidden / (gu_ms * 1e-3) / 1e12}
+    # mixed-precision stack: 2-bit codes in the even layers, the 4-bit layers of the main run in the odd ones
+    if layers4 is not None:
+        mixed = []
+        for l in range(L):
+            if l % 2 == 0:
+                t = si.layer_tensors(shape, l, 0, device=dev)
+                mixed.append(qt.quantize_layer(t, 2, shape.group, keep_canonical=False))
+                del t
+            else:
+                mixed.append(layers4[l])
+        mstack = qt.Stack(cfg, mixed)
+        qt.qtale_stack_forward(ctx, mstack, xs[0], offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            qt.qtale_stack_forward(ctx, mstack, xs[1], offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        out["mixed_2_4_bit_prefill_tokens_per_s"] = T * 3 / (time.perf_counter() - t0)
+        del mstack, mixed
     del xs, ws
     if not no_decode:
         out["decode"] = decode_section(qt, si, torch, layers, L, bits=3, ratios=(1.0, 0.4))["by_exec_ratio"]
@@ -362,7 +381,7 @@ def main():
     del xs, ws
     int3 = None
     if not args.no_int3:
-        int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode)
+        int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode, layers)
     decode = None
     if not args.no_decode:
         decode = decode_section(qt, si, torch, layers, L)

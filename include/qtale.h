@@ -78,7 +78,8 @@ int qtale_get_control(const qtale_ctx* ctx, int* mode /*host*/, float* value /*h
  *   zeros     [N][ceil(K/group)] fp16 bit patterns of the integer zero-point
  *   prepacked the kernels' private copy (codes reordered for the matrix-core operand layout plus
  *             scale/zero pairs), qtale_prepacked_bytes() bytes, 16-byte aligned; may be NULL here.
- * Supported: bits in {4, 3} (Sec. 4.1 evaluates both); group in {32, 64, 128}; K % 8 == 0.  Else
+ * Supported: bits in {4, 3} (Sec. 4.1 evaluates both) and 2 (for mixed 2-/4-bit stacks: 16 codes per word,
+ * bit pair j of word w = code of k = 16*w + j); group in {32, 64, 128}; K % 8 == 0.  Else
  * QTALE_ERR_UNSUPPORTED / _SHAPE.
  * The GEMM entry points (forward calls, qtale_linear_w4a16, qtale_swiglu_w4a16) also need N % 8 == 0. */
 size_t qtale_prepacked_bytes(int N, int K, int bits, int group);
@@ -99,7 +100,7 @@ typedef struct {
 
 typedef struct {
     int hidden, n_heads, n_kv_heads, head_dim, inter;   /* head_dim must be 64 or 128 */
-    int bits;                                           /* 4 or 3: code width of all seven linears */
+    int bits;                                           /* 4, 3 or 2: default code width of the seven linears */
     int group;                                          /* 32, 64 or 128 */
     int act_dtype;                                      /* QTALE_ACT_FP16 | QTALE_ACT_BF16 */
     float rms_eps;                                      /* e.g. 1e-5 */
@@ -121,6 +122,7 @@ typedef struct {
     const float* router_b1;                    /* [R] fp32 */
     const float* router_w2;                    /* [2][R] fp32: row 0 execute logit, row 1 bypass logit */
     const float* router_b2;                    /* [2] fp32 */
+    int bits;                                  /* code width of THIS layer's linears; 0 = cfg->bits (mixed-precision stacks) */
 } qtale_layer_weights;
 
 /* Per-layer K/V cache holding entries of EXECUTED tokens only (a bypassed token produces no key or

@@ -50,7 +50,7 @@ class qtale_layer_weights(C.Structure):
                 ("gate", qtale_qlinear), ("up", qtale_qlinear), ("down", qtale_qlinear),
                 ("norm1", C.c_void_p), ("norm2", C.c_void_p), ("router_w", C.c_void_p), ("router_b", C.c_float),
                 ("router_hidden", C.c_int), ("router_w1", C.c_void_p), ("router_b1", C.c_void_p),
-                ("router_w2", C.c_void_p), ("router_b2", C.c_void_p)]
+                ("router_w2", C.c_void_p), ("router_b2", C.c_void_p), ("bits", C.c_int)]
 
 
 class qtale_kv(C.Structure):
@@ -181,7 +181,7 @@ class QuantLinear:
 
 def canonical_words(K, bits):
     """uint32 words per row of the canonical code array."""
-    return 3 * ((K + 31) // 32) if bits == 3 else (K + 7) // 8
+    return 3 * ((K + 31) // 32) if bits == 3 else (K + 15) // 16 if bits == 2 else (K + 7) // 8
 
 
 def qtale_quantize(W, bits=4, group=128, keep_canonical=True):
@@ -233,7 +233,8 @@ class LayerWeights:
                                    self.norm1.data_ptr(), self.norm2.data_ptr(),
                                    self.router_w.data_ptr() if self.router_w is not None else None, self.router_b,
                                    *((0, None, None, None, None) if self.router_mlp is None else
-                                     (self.router_mlp[0].shape[0],) + tuple(t.data_ptr() for t in self.router_mlp)))
+                                     (self.router_mlp[0].shape[0],) + tuple(t.data_ptr() for t in self.router_mlp)),
+                                   l["q"].bits)
 
 
 class KVCache:

@@ -20,7 +20,7 @@ struct GemmDev {
     const void* resid;
     const int32_t* idx;
     int bf16;
-    int bits;                      // 4 or 3: width of the weight codes
+    int bits;                      // 4, 3 or 2: width of the weight codes
 };
 
 constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
@@ -116,7 +116,40 @@ __device__ __forceinline__ half2_t dequant_pair3(const u32x3_t& t, int h, const 
     return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(w9, 0x00380038u, magic)), eighth, -s.Z3) * s.S;
 }
 
-// ---- the two code widths behind one interface -----------------------------------------------------------
+// ---- 2-bit codes -------------------------------------------------------------------------------------
+// A lane's 32 codes of one fragment x k-tile occupy two words; pair h (codes 2h, 2h+1) sits in word h/8 at bit
+// 2*(h%8) of the low half (even code) and of the high half (odd code).  Fields at bits 0, 2, 4 are OR-ed into
+// 0x6400 directly (1024 + c, 1024 + 4c, 1024 + 16c), the others after a shift by 6 or 12.
+struct ScaleZero2 {
+    half2_t S, Z0, Z1, Z2;
+};
+__device__ __forceinline__ ScaleZero2 expand_sz2(uint32_t raw) {
+    const half2_t sz = __builtin_bit_cast(half2_t, raw);
+    ScaleZero2 r;
+    r.S = half2_t{sz[0], sz[0]};
+    const half_t z0 = sz[1] + static_cast<half_t>(1024.0f);
+    const half_t z1 = sz[1] + static_cast<half_t>(256.0f);
+    const half_t z2 = sz[1] + static_cast<half_t>(64.0f);
+    r.Z0 = half2_t{z0, z0};
+    r.Z1 = half2_t{z1, z1};
+    r.Z2 = half2_t{z2, z2};
+    return r;
+}
+
+// Pair h of the lane's tile (h must fold to a constant after unrolling).
+__device__ __forceinline__ half2_t dequant_pair2(const u32x2_t& t, int h, const ScaleZero2& s, uint32_t magic) {
+    const half2_t quarter = {static_cast<half_t>(0.25f), static_cast<half_t>(0.25f)};
+    const half2_t sixteenth = {static_cast<half_t>(0.0625f), static_cast<half_t>(0.0625f)};
+    const int slot = h & 7;
+    const uint32_t w = (h >> 3) == 0 ? t.x : t.y;
+    const uint32_t src = slot < 3 ? w : slot < 6 ? (w >> 6) : (w >> 12);
+    const int f = slot < 3 ? slot : slot < 6 ? slot - 3 : slot - 6;
+    if (f == 0) return (__builtin_bit_cast(half2_t, and_or(src, 0x00030003u, magic)) - s.Z0) * s.S;
+    if (f == 1) return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(src, 0x000c000cu, magic)), quarter, -s.Z1) * s.S;
+    return __builtin_elementwise_fma(__builtin_bit_cast(half2_t, and_or(src, 0x00300030u, magic)), sixteenth, -s.Z2) * s.S;
+}
+
+// ---- the code widths behind one interface ---------------------------------------------------------------
 // WBits<BITS>: register type of a lane's packed codes for one fragment x k-tile, bytes per lane, expanded
 // scale/zero constants, the load and the dequantisation of k-step j (8 weights in operand order).
 template <int BITS>
@@ -134,6 +167,27 @@ struct WBits<4> {
     static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
         const uint32_t w = j == 0 ? t.x : j == 1 ? t.y : j == 2 ? t.z : t.w;
         return dequant8(w, s.S, s.Zlo, s.Zhi, magic);
+    }
+};
+
+template <>
+struct WBits<2> {
+    using Tile = u32x2_t;
+    using SZ = ScaleZero2;
+    static constexpr int kLaneBytes = 8;
+    static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
+        return (reinterpret_cast<const u32x2_t*>(frag_base) + static_cast<size_t>(kt) * 64)[lane];
+    }
+    static __device__ __forceinline__ SZ expand(uint32_t raw) { return expand_sz2(raw); }
+    static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
+        const half2_t p0 = dequant_pair2(t, 4 * j + 0, s, magic);
+        const half2_t p1 = dequant_pair2(t, 4 * j + 1, s, magic);
+        const half2_t p2 = dequant_pair2(t, 4 * j + 2, s, magic);
+        const half2_t p3 = dequant_pair2(t, 4 * j + 3, s, magic);
+        half8_t r;
+        r[0] = p0[0]; r[1] = p0[1]; r[2] = p1[0]; r[3] = p1[1];
+        r[4] = p2[0]; r[5] = p2[1]; r[6] = p3[0]; r[7] = p3[1];
+        return r;
     }
 };
 

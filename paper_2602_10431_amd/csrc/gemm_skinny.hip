@@ -279,6 +279,10 @@ hipError_t launch_gemm_skinny(GemmDev& d, int epilogue, hipStream_t stream) {
         if (d.gshift == 5) return launch_gpt<3, 2>(d, epilogue, stream);
         return launch_gpt<3, 1>(d, epilogue, stream);
     }
+    if (d.bits == 2) {
+        if (d.gshift == 5) return launch_gpt<2, 2>(d, epilogue, stream);
+        return launch_gpt<2, 1>(d, epilogue, stream);
+    }
     if (d.gshift == 5) return launch_gpt<4, 2>(d, epilogue, stream);
     return launch_gpt<4, 1>(d, epilogue, stream);
 }

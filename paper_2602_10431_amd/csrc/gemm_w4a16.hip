@@ -407,6 +407,10 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
         if (a.group == 32) return launch_gpt<3, 2>(d, a.epilogue, stream);
         return launch_gpt<3, 1>(d, a.epilogue, stream);
     }
+    if (a.bits == 2) {
+        if (a.group == 32) return launch_gpt<2, 2>(d, a.epilogue, stream);
+        return launch_gpt<2, 1>(d, a.epilogue, stream);
+    }
     if (a.group == 32) return launch_gpt<4, 2>(d, a.epilogue, stream);
     return launch_gpt<4, 1>(d, a.epilogue, stream);
 }

@@ -76,7 +76,7 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
 
 int check_quant_params(int N, int K, int bits, int group) {
     if (N <= 0 || K <= 0) return QTALE_ERR_INVALID_ARG;
-    if (bits != 4 && bits != 3) return QTALE_ERR_UNSUPPORTED;
+    if (bits != 4 && bits != 3 && bits != 2) return QTALE_ERR_UNSUPPORTED;
     if (group != 32 && group != 64 && group != 128) return QTALE_ERR_UNSUPPORTED;
     if (K % 8 != 0) return QTALE_ERR_SHAPE;
     return QTALE_OK;
@@ -86,7 +86,7 @@ int check_cfg(const qtale_layer_cfg* c) {
     if (!c) return QTALE_ERR_INVALID_ARG;
     if (c->hidden <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->inter <= 0)
         return QTALE_ERR_INVALID_ARG;
-    if (c->bits != 4 && c->bits != 3) return QTALE_ERR_UNSUPPORTED;
+    if (c->bits != 4 && c->bits != 3 && c->bits != 2) return QTALE_ERR_UNSUPPORTED;
     if (c->group != 32 && c->group != 64 && c->group != 128) return QTALE_ERR_UNSUPPORTED;
     if (c->head_dim != 64 && c->head_dim != 128) return QTALE_ERR_UNSUPPORTED;
     if (c->act_dtype != QTALE_ACT_FP16 && c->act_dtype != QTALE_ACT_BF16) return QTALE_ERR_UNSUPPORTED;
@@ -114,6 +114,7 @@ int check_weights(const qtale_layer_cfg* c, const qtale_layer_weights* w) {
     if ((e = check_linear(w->up, c->inter, H))) return e;
     if ((e = check_linear(w->down, H, c->inter))) return e;
     if (!w->norm1 || !w->norm2) return QTALE_ERR_INVALID_ARG;
+    if (w->bits != 0 && w->bits != 4 && w->bits != 3 && w->bits != 2) return QTALE_ERR_UNSUPPORTED;
     if (w->router_hidden < 0 || w->router_hidden > 256) return QTALE_ERR_INVALID_ARG;
     if (w->router_hidden > 0) {
         if (!w->router_w1 || !w->router_b1 || !w->router_w2 || !w->router_b2) return QTALE_ERR_INVALID_ARG;
@@ -181,6 +182,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     const int bf16 = c->act_dtype == QTALE_ACT_BF16;
     const int H = c->hidden, nh = c->n_heads, nkv = c->n_kv_heads, d = c->head_dim, I = c->inter;
     const int ratio_mode = ctx->mode == QTALE_MODE_RATIO;
+    const int lbits = w->bits ? w->bits : c->bits;     // per-layer code width (mixed-precision stacks)
     const int k = ratio_mode ? executed_count(ctx->value, T) : 0;
     const int M_max = ratio_mode ? k : T;
     float* z = scores ? scores : ws.z;
@@ -214,7 +216,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 3);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 3;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = lbits; g.n_w = 3;
         g.w[0] = {w->q.prepacked, w->q.N, w->q.K};
         g.w[1] = {w->k.prepacked, w->k.N, w->k.K};
         g.w[2] = {w->v.prepacked, w->v.N, w->v.K};
@@ -242,7 +244,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 6);
         GemmArgs g{};
-        g.A = ws.attn; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = nh * d; g.group = c->group; g.bits = c->bits; g.n_w = 1;
+        g.A = ws.attn; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = nh * d; g.group = c->group; g.bits = lbits; g.n_w = 1;
         g.w[0] = {w->o.prepacked, w->o.N, w->o.K};
         g.epilogue = EPI_RESID_F32; g.out = ws.h; g.ldo = H; g.resid = x; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));
@@ -254,7 +256,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 8);
         GemmArgs g{};
-        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = c->bits; g.n_w = 2;
+        g.A = ws.nbuf; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = H; g.group = c->group; g.bits = lbits; g.n_w = 2;
         g.w[0] = {w->gate.prepacked, w->gate.N, w->gate.K};
         g.w[1] = {w->up.prepacked, w->up.N, w->up.K};
         g.epilogue = EPI_SWIGLU_F16; g.out = ws.act; g.ldo = I;
@@ -263,7 +265,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     {
         Prof pr(ctx, stream, 9);
         GemmArgs g{};
-        g.A = ws.act; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = I; g.group = c->group; g.bits = c->bits; g.n_w = 1;
+        g.A = ws.act; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = I; g.group = c->group; g.bits = lbits; g.n_w = 1;
         g.w[0] = {w->down.prepacked, w->down.N, w->down.K};
         g.epilogue = EPI_RESID_SCATTER; g.out = x; g.ldo = H; g.resid = ws.h; g.idx = ws.idx; g.bf16 = bf16;
         HIP_TRY(launch_gemm_w4a16(g, stream));

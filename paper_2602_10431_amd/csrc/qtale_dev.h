@@ -11,6 +11,7 @@ typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16-byte register value (first-class, unlike a struct)
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));   // 8 bytes of packed 2-bit codes
 typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));   // 12 bytes of packed 3-bit codes (register value)
 typedef float float16_t __attribute__((ext_vector_type(16)));
 

@@ -64,6 +64,10 @@ quantize_rows_kernel(const float* __restrict__ W, int N, int K, int bits, int gr
         const int blk = w >> 2;                       // 32-code block of the row; its first thread has k0 = 32*blk
         if (row_ok && i < 3 && blk * 32 < K)
             codes[static_cast<size_t>(n) * (3 * ((K + 31) >> 5)) + 3 * blk + i] = out;
+    } else if (bits == 2) {                           // two consecutive threads hold one word (16 codes)
+        const int lane = threadIdx.x & 63;
+        const uint32_t lo16 = __shfl(word, lane & ~1, 64), hi16 = __shfl(word, lane | 1, 64);
+        if (ok && (lane & 1) == 0) codes[static_cast<size_t>(n) * ((K + 15) >> 4) + (w >> 1)] = lo16 | (hi16 << 16);
     } else if (ok) {
         codes[static_cast<size_t>(n) * ((K + 7) >> 3) + w] = word;
     }
@@ -196,12 +200,60 @@ prepack3_kernel(const uint32_t* __restrict__ codes, const uint16_t* __restrict__
     }
 }
 
+// 2-bit codes.  Same fragment / k-tile order, 8 bytes per lane: pair h = q/2 of the lane's 32 codes sits in word
+// h/8 at bit 2*(h%8) of the low half (even code) and of the high half (odd code).  sz as above.
+__global__ void __launch_bounds__(256)
+prepack2_kernel(const uint32_t* __restrict__ codes, const uint16_t* __restrict__ scales,
+                const uint16_t* __restrict__ zeros, int N, int K, int group, int n_groups,
+                int NF, int KT, int NGP, uint32_t* __restrict__ pcodes, uint32_t* __restrict__ psz) {
+    const long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const long n_code = static_cast<long>(NF) * KT * 64;
+    const int kw = (K + 15) >> 4;
+    if (gid < n_code) {
+        const int lane = static_cast<int>(gid & 63);
+        const long t = gid >> 6;
+        const int kt = static_cast<int>(t % KT);
+        const int f = static_cast<int>(t / KT);
+        const int n = f * 32 + (lane & 31);
+        uint32_t out[2] = {0u, 0u};
+        for (int q = 0; q < 32; ++q) {
+            const int k = kt * 64 + (q >> 3) * 16 + (lane >> 5) * 8 + (q & 7);
+            uint32_t c = 0;
+            if (n < N) {
+                if (k < K) {
+                    c = (codes[static_cast<size_t>(n) * kw + (k >> 4)] >> (2 * (k & 15))) & 3u;
+                } else {
+                    const int g = k / group;
+                    c = g < n_groups
+                        ? static_cast<uint32_t>(static_cast<float>(__builtin_bit_cast(half_t, zeros[static_cast<size_t>(n) * n_groups + g])))
+                        : 0u;
+                }
+            }
+            const int h = q >> 1;
+            out[h >> 3] |= c << (2 * (h & 7) + (q & 1) * 16);
+        }
+        pcodes[gid * 2 + 0] = out[0];
+        pcodes[gid * 2 + 1] = out[1];
+    }
+    const long n_sz = static_cast<long>(NGP) * NF * 32;
+    if (gid < n_sz) {
+        const int n = static_cast<int>(gid % (NF * 32));
+        const int g = static_cast<int>(gid / (NF * 32));
+        uint32_t v = 0;
+        if (n < N && g < n_groups) {
+            v = static_cast<uint32_t>(scales[static_cast<size_t>(n) * n_groups + g]) |
+                (static_cast<uint32_t>(zeros[static_cast<size_t>(n) * n_groups + g]) << 16);
+        }
+        psz[gid] = v;
+    }
+}
+
 PrepackDims prepack_dims(int N, int K, int group, int bits) {
     PrepackDims d;
     d.NF = (N + 31) / 32;
     d.KT = (K + 63) / 64;
     d.NGP = (d.KT * 64 + group - 1) / group;
-    d.code_bytes = static_cast<size_t>(d.NF) * d.KT * (bits == 3 ? 768 : 1024);
+    d.code_bytes = static_cast<size_t>(d.NF) * d.KT * (bits == 3 ? 768 : bits == 2 ? 512 : 1024);
     d.sz_bytes = static_cast<size_t>(d.NGP) * d.NF * 32 * 4;
     return d;
 }
@@ -228,6 +280,11 @@ hipError_t launch_prepack(const uint32_t* codes, const uint16_t* scales, const u
     if (blocks == 0) return hipSuccess;
     U4* pc = reinterpret_cast<U4*>(prepacked);
     uint32_t* ps = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(prepacked) + d.code_bytes);
+    if (bits == 2) {
+        hipLaunchKernelGGL(prepack2_kernel, dim3(blocks), dim3(256), 0, stream, codes, scales, zeros, N, K,
+                           group, ng, d.NF, d.KT, d.NGP, reinterpret_cast<uint32_t*>(prepacked), ps);
+        return hipGetLastError();
+    }
     if (bits == 3) {
         hipLaunchKernelGGL(prepack3_kernel, dim3(blocks), dim3(256), 0, stream, codes, scales, zeros, N, K,
                            group, ng, d.NF, d.KT, d.NGP, reinterpret_cast<uint32_t*>(prepacked), ps);

@@ -63,7 +63,8 @@ def test_size_queries(qt):
     assert n == 4096 * 11008 // 2 + 4 * 4096 * (11008 // 128)
     # 3-bit codes: 12 bytes per lane per k-tile, same scale/zero section
     assert qt.qtale_prepacked_bytes(4096, 11008, 3, 128) == 4096 * 11008 * 3 // 8 + 4 * 4096 * (11008 // 128)
-    assert qt.qtale_prepacked_bytes(4096, 11008, 2, 128) == 0
+    assert qt.qtale_prepacked_bytes(4096, 11008, 2, 128) == 4096 * 11008 // 4 + 4 * 4096 * (11008 // 128)
+    assert qt.qtale_prepacked_bytes(4096, 11008, 5, 128) == 0
     assert qt.qtale_prepacked_bytes(4096, 11008, 4, 100) == 0
     assert qt.qtale_prepacked_bytes(4096, 11006, 4, 128) == 0
     cfg = qt.make_cfg(4096, 32, 32, 128, 11008)
@@ -89,7 +90,7 @@ def test_forward_argument_validation_needs_no_gpu(qt):
     assert call(cfg, T=-1) == -1
     assert call(cfg) == -1                                       # weights without prepacked buffers
     assert call(qt.make_cfg(256, 4, 3, 64, 688, group=32)) == -2  # heads not divisible
-    assert call(qt.make_cfg(256, 4, 4, 64, 688, bits=2, group=32)) == -3
+    assert call(qt.make_cfg(256, 4, 4, 64, 688, bits=5, group=32)) == -3
     assert call(qt.make_cfg(256, 4, 4, 64, 688, group=48)) == -3
     assert call(qt.make_cfg(256, 4, 4, 80, 688, group=32)) == -3
     assert call(qt.make_cfg(250, 4, 4, 64, 688, group=32)) == -2

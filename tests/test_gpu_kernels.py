@@ -25,7 +25,7 @@ def _w(N, K, seed, std=0.02):
     return torch.randn(N, K, generator=g) * std
 
 
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2])
 @pytest.mark.parametrize("N,K,G", [(256, 256, 32), (256, 688, 32), (688, 256, 32), (100, 136, 64),
                                    (512, 1024, 128), (33, 4096, 128), (4096, 264, 128)])
 def test_quantize_is_bit_exact(qt, N, K, G, bits):
@@ -42,7 +42,7 @@ def test_quantize_is_bit_exact(qt, N, K, G, bits):
 
 def test_quantize_rejects_bad_parameters(qt):
     W = _w(8, 64, 0).cuda()
-    for bits, group in [(2, 128), (5, 128), (4, 48), (8, 128)]:
+    for bits, group in [(1, 128), (5, 128), (4, 48), (8, 128)]:
         with pytest.raises(qt.QtaleError):
             qt.qtale_quantize(W, bits, group)
     with pytest.raises(qt.QtaleError):
@@ -52,7 +52,7 @@ def test_quantize_rejects_bad_parameters(qt):
 @pytest.mark.parametrize("M,N,K,G", [(64, 256, 256, 32), (32, 256, 688, 32), (7, 688, 256, 32), (300, 416, 512, 128),
                                      (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128),
                                      (65, 4096, 1024, 128), (130, 416, 688, 32), (256, 1024, 512, 64)])
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2])
 def test_linear_w4a16_matches_oracle(qt, M, N, K, G, bits):
     W = _w(N, K, M + N + K)
     A = torch.randn(M, K, generator=torch.Generator().manual_seed(M)).to(torch.float16)
@@ -64,7 +64,7 @@ def test_linear_w4a16_matches_oracle(qt, M, N, K, G, bits):
     assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
 
 
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2])
 @pytest.mark.parametrize("M,K,N,G", [(256, 256, 96, 32), (64, 64, 512, 64), (512, 512, 40, 128)])
 def test_identity_activations_return_the_dequantized_weights_exactly(qt, M, K, N, G, bits):
     # A = I: out[m][n] is the single product 1 * W'[n][m], so the kernel's in-register dequantisation
@@ -93,7 +93,7 @@ def test_prepack_from_canonical_three_bit_codes(qt):
 
 
 @pytest.mark.parametrize("M,I,K,G", [(64, 688, 256, 32), (200, 352, 512, 128), (5, 64, 128, 64)])
-@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("bits", [4, 3, 2])
 def test_swiglu_w4a16_matches_oracle(qt, M, I, K, G, bits):
     Wg, Wu = _w(I, K, 1, 0.05), _w(I, K, 2, 0.05)
     A = torch.randn(M, K, generator=torch.Generator().manual_seed(3)).to(torch.float16)

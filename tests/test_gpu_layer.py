@@ -197,6 +197,40 @@ def test_stack_teacher_forced(qt):
             assert orc.parity_error(to_f64(xout)[widx], want[widx]) <= TOL
 
 
+def test_mixed_two_and_four_bit_stack_teacher_forced(qt):
+    # interleaved 2-bit / 4-bit layers (the mixed-precision variant of the paper's appendix): every layer carries
+    # its own code width, the stack call is the same
+    import dataclasses
+    base = si.LayerShape(256, 4, 2, 64, 688, 4, 32, "fp16")
+    L, T, seed = 4, 160, 27
+    shapes = [dataclasses.replace(base, bits=2 if l % 2 == 0 else 4) for l in range(L)]
+    layers_t = [si.layer_tensors(shapes[l], l, seed, unit_gains=False, std=0.06) for l in range(L)]
+    x = si.hidden_states(base, T, seed)
+    offs, pos = si.ragged_sequences([100, 60])
+    stack = qt.Stack(qt.cfg_from_shape(base), [qt.quantize_layer(t, shapes[l].bits, base.group) for l, t in enumerate(layers_t)])
+    ctx = qt.Context()
+    qt.qtale_set_exec_ratio(ctx, 0.6)
+    xg = x.cuda()
+    idx = torch.full((L, T), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(L, dtype=torch.int32, device="cuda")
+    dbg = torch.empty((L, T, base.hidden), dtype=x.dtype, device="cuda")
+    qt.qtale_stack_forward(ctx, stack, xg, offs.cuda(), pos.cuda(), sel_idx=idx, sel_count=cnt, dbg_hidden=dbg)
+    torch.cuda.synchronize()
+    for l in range(L):
+        p, _ = oracle_layer(shapes[l], l, seed, tensors=layers_t[l])
+        xin = dbg[l].cpu()
+        xout = (dbg[l + 1] if l + 1 < L else xg).cpu()
+        want, widx, _ = orc.layer_forward(to_f64(xin), p, cfg_dict(base), offs.numpy(), pos.numpy(), "ratio", 0.6)
+        k = int(cnt[l].item())
+        assert k == len(widx) and np.array_equal(idx[l, :k].cpu().numpy(), widx)
+        assert orc.parity_error(to_f64(xout)[widx], want[widx]) <= TOL
+
+
+def test_two_bit_layer_group128_bf16(qt):
+    shape = si.LayerShape(512, 4, 2, 128, 1408, 2, 128, "bf16")
+    _check_layer(qt, shape, 333, [100, 1, 200, 32], "ratio", 0.6, seed=28, std=0.057, starts=[0, 5, 17, 1000])
+
+
 def test_ratio_change_leaves_weights_untouched(qt):
     shape = si.C1
     tensors = si.layer_tensors(shape, 0, 8)
