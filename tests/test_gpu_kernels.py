@@ -181,3 +181,48 @@ def test_mlp_router_scores_are_bit_exact(qt, T, H, R, dtype):
     want = orc.router_scores_mlp(x.to(torch.float64).numpy(), W1.numpy(), b1.numpy(), W2.numpy(), b2.numpy())
     assert np.array_equal(z.cpu().numpy().view(np.uint32), want.view(np.uint32))
 
+
+def test_linear_random_shape_sweep(qt):
+    # 40 seeded shapes across the dispatch regimes (few rows / 64-row chunks / 128-row tiles), ragged K, output
+    # widths that are not multiples of the 32-column fragment, all code widths and group sizes
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        bits = int(rng.choice([4, 3, 2]))
+        G = int(rng.choice([32, 64, 128]))
+        M = int(rng.choice([1, 3, 17, 31, 33, 64, 65, 100, 129, 200, 256, 257, 300, 520]))
+        N = 8 * int(rng.integers(1, 90))
+        K = 8 * int(rng.integers(2, 140))
+        g = torch.Generator().manual_seed(1000 + case)
+        W = torch.randn(N, K, generator=g) * 0.05
+        A = torch.randn(M, K, generator=g).to(torch.float16)
+        ql = qt.qtale_quantize(W.cuda(), bits, G)
+        out = qt.qtale_linear_w4a16(ql, A.cuda())
+        torch.cuda.synchronize()
+        codes, s, z = orc.quantize_rtn(W.numpy(), bits, G)
+        assert np.array_equal(ql.codes.cpu().numpy().view(np.uint32), orc.pack_codes(codes, bits)), (case, bits, G, N, K)
+        want = A.to(torch.float64).numpy() @ orc.dequantize(codes, s, z, G).T
+        err = orc.parity_error(out.cpu().to(torch.float64).numpy(), want)
+        assert err <= TOL, (case, bits, G, M, N, K, err)
+
+
+def test_swiglu_random_shape_sweep(qt):
+    rng = np.random.default_rng(77)
+    for case in range(16):
+        bits = int(rng.choice([4, 3, 2]))
+        G = int(rng.choice([32, 64, 128]))
+        M = int(rng.choice([1, 30, 64, 70, 190, 256, 300]))
+        I = 8 * int(rng.integers(1, 120))
+        K = 8 * int(rng.integers(2, 100))
+        g = torch.Generator().manual_seed(2000 + case)
+        Wg, Wu = torch.randn(I, K, generator=g) * 0.05, torch.randn(I, K, generator=g) * 0.05
+        A = torch.randn(M, K, generator=g).to(torch.float16)
+        qg, qu = qt.qtale_quantize(Wg.cuda(), bits, G), qt.qtale_quantize(Wu.cuda(), bits, G)
+        out = qt.qtale_swiglu_w4a16(qg, qu, A.cuda())
+        torch.cuda.synchronize()
+        A64 = A.to(torch.float64).numpy()
+        dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), bits, G), G)
+        du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), bits, G), G)
+        want = orc.silu(A64 @ dg.T) * (A64 @ du.T)
+        err = orc.parity_error(out.cpu().to(torch.float64).numpy(), want)
+        assert err <= TOL, (case, bits, G, M, I, K, err)
+

@@ -151,6 +151,26 @@ def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
         assert np.array_equal(gk[b, n1:], to_f64(kc)[b, n1:])    # nothing written past the new length
 
 
+def test_random_cache_scenarios(qt):
+    # seeded scenarios: ragged (also empty) sequences appended to caches of random fill, random ratio, head
+    # layout and code width
+    rng = np.random.default_rng(99)
+    for case in range(10):
+        nkv = int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([64, 128]))
+        nh = nkv * int(rng.choice([1, 2, 4]))
+        H = int(rng.choice([128, 256]))
+        shape = si.LayerShape(H, nh, nkv, d, 8 * int(rng.integers(8, 60)), int(rng.choice([4, 3, 2])),
+                              int(rng.choice([32, 64])), str(rng.choice(["fp16", "bf16"])))
+        B = int(rng.integers(1, 6))
+        lens = [int(v) for v in rng.integers(0, 40, size=B)]
+        if sum(lens) == 0:
+            lens[0] = 5
+        old = [int(v) for v in rng.integers(0, 50, size=B)]
+        cap = max(o + n for o, n in zip(old, lens)) + int(rng.integers(0, 4))
+        _cache_case(qt, shape, lens, old, old, max(cap, 1), 300 + case, float(rng.choice([0.3, 0.5, 0.8, 1.0])))
+
+
 def test_decode_step_with_cache(qt):
     # one new token per sequence against cached context; skipped tokens append nothing
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "fp16")
