@@ -379,6 +379,28 @@ def main():
                "router_fp64_TFLOPs": 2.0 * T * shape.hidden * 16 / (r_ms * 1e-3) / 1e12}
         del mlp_stack, mlp_layers
     del xs, ws
+    # one 1024-token prompt through the same stack: a few hundred executed rows per layer, where the
+    # hidden-size-wide linears run on 64-row tiles
+    single = None
+    if not args.no_sweep:
+        S1 = 1024
+        o1, p1 = si.equal_sequences(1, S1)
+        o1, p1 = o1.to(dev), p1.to(dev)
+        ws1 = qt.alloc_workspace(cfg, S1, 1, dev)
+        single = {"workload": "same stack, one prompt of %d tokens" % S1, "by_exec_ratio": {}}
+        for r in (1.0, 0.5, 0.3):
+            qt.qtale_set_exec_ratio(ctx, r)
+            xs = [si.hidden_states(shape, S1, 0, extra=7000 + i, device=dev) for i in range(9)]
+            qt.qtale_stack_forward(ctx, stack, xs[0], o1, p1, workspace=ws1)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for x in xs[1:]:
+                qt.qtale_stack_forward(ctx, stack, x, o1, p1, workspace=ws1)
+            torch.cuda.synchronize()
+            dt1 = (time.perf_counter() - t0) / 8
+            single["by_exec_ratio"]["%.1f" % r] = {"tokens_per_s": S1 / dt1, "ms_per_step": dt1 * 1e3}
+        qt.qtale_set_exec_ratio(ctx, args.ratio)
+        del xs, ws1
     int3 = None
     if not args.no_int3:
         int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode, layers)
@@ -403,6 +425,7 @@ def main():
         "tokens_per_s_vs_exec_ratio": sweep,
         "threshold_mode": threshold,
         "mlp_router": mlp,
+        "single_prompt": single,
         "decode": decode,
         "int3": int3,
     }

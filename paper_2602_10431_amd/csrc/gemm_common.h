@@ -233,6 +233,103 @@ __device__ __forceinline__ void map_fragment(const GemmDev& p, int vf, int& mat,
     }
 }
 
+// Epilogue of the tiled kernels.  A wave holds FM x FN accumulator fragments (rows row_base + fm*32 ...,
+// virtual fragments vf0 ... vf0 + FN - 1).  Accumulator register r of a lane holds C[row][col] with
+// col = lane%32 and row = 8*(r/4) + 4*(lane/32) + r%4 inside a 32x32 fragment.  The wave transposes one
+// 32-row slab at a time through its private LDS region `Cs` (32 x (columns + 8) floats) so that global
+// traffic is row-contiguous: a lane then owns 4 consecutive columns of one row (16-byte fp32 / 8-byte
+// 16-bit accesses, 128+ contiguous bytes per row per wave).  The four epilogues fuse what follows the
+// linear: fp16 store (q|k|v), residual add from the gathered rows of x into an fp32 h (o-proj),
+// SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
+template <int EPI, int FM, int FN>
+__device__ __forceinline__ void store_tile(const GemmDev& p, const float16_t (&acc)[FM][FN], float* Cs, int lane,
+                                           int row_base, int vf0, int M) {
+    constexpr int NFO = EPI == EPI_SWIGLU_F16 ? FN / 2 : FN;   // output fragments per wave
+    constexpr int CW = NFO * 32;                               // output columns per wave
+    constexpr int CSTR = CW + 8;                               // slab row stride (floats): conflict-free writes
+    constexpr int LPR = CW / 4;                                // lanes per row when reading back
+    constexpr int RPP = 64 / LPR;                              // rows per pass
+    constexpr int PASSES = 32 / RPP;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int rr = lane / LPR;                                 // row inside a pass
+    const int c4 = (lane % LPR) * 4;                           // first of this lane's 4 columns in the slab
+    // which output fragment / matrix the lane's columns belong to
+    const int fo = c4 >> 5;
+    const int o_vf = vf0 + (EPI == EPI_SWIGLU_F16 ? 2 * fo : fo);
+    const bool o_valid = o_vf < p.vf_total;
+    int o_mat = 0, o_f = o_vf;
+    map_fragment<EPI>(p, o_vf, o_mat, o_f);
+    const int o_ncol = o_f * 32 + (c4 & 31);
+    const bool col_ok = o_valid && o_ncol < p.N[o_mat];        // N % 4 == 0: the 4 columns are all in or all out
+    const int col = (EPI == EPI_SWIGLU_F16 ? 0 : p.colbase[o_mat]) + o_ncol;
+    const int32_t* __restrict__ idx = p.idx;
+
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+#pragma unroll
+        for (int f = 0; f < NFO; ++f) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v;
+                if (EPI == EPI_SWIGLU_F16) v = silu_f(acc[fm][2 * f][r]) * acc[fm][2 * f + 1][r];
+                else v = acc[fm][f][r];
+                Cs[(8 * (r >> 2) + 4 * lhi + (r & 3)) * CSTR + f * 32 + l32] = v;
+            }
+        }
+        const int row0 = row_base + fm * 32 + rr;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ps += 4) {
+            float4 v[4], res[4];
+            uint2 xr[4];
+            int trow[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = row0 + (ps + u) * RPP;
+                ok[u] = col_ok && row < M;
+                v[u] = *reinterpret_cast<const float4*>(&Cs[((ps + u) * RPP + rr) * CSTR + c4]);
+                trow[u] = row;
+                if (EPI == EPI_RESID_F32 || EPI == EPI_RESID_SCATTER) trow[u] = ok[u] ? idx[row] : 0;
+            }
+            if (EPI == EPI_RESID_F32) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) xr[u] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(p.resid) + static_cast<size_t>(trow[u]) * p.ldo + col);
+            } else if (EPI == EPI_RESID_SCATTER) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) res[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.resid) + static_cast<size_t>(row0 + (ps + u) * RPP) * p.ldo + col);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (!ok[u]) continue;
+                const int row = row0 + (ps + u) * RPP;
+                if (EPI == EPI_STORE_F16 || EPI == EPI_SWIGLU_F16) {
+                    uint2 o;
+                    o.x = static_cast<uint32_t>(float_to_half_bits(v[u].x)) | (static_cast<uint32_t>(float_to_half_bits(v[u].y)) << 16);
+                    o.y = static_cast<uint32_t>(float_to_half_bits(v[u].z)) | (static_cast<uint32_t>(float_to_half_bits(v[u].w)) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
+                } else if (EPI == EPI_RESID_F32) {
+                    float4 o;
+                    o.x = act_to_float(static_cast<uint16_t>(xr[u].x & 0xffffu), p.bf16) + v[u].x;
+                    o.y = act_to_float(static_cast<uint16_t>(xr[u].x >> 16), p.bf16) + v[u].y;
+                    o.z = act_to_float(static_cast<uint16_t>(xr[u].y & 0xffffu), p.bf16) + v[u].z;
+                    o.w = act_to_float(static_cast<uint16_t>(xr[u].y >> 16), p.bf16) + v[u].w;
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + static_cast<size_t>(row) * p.ldo + col) = o;
+                } else {
+                    uint2 o;
+                    o.x = static_cast<uint32_t>(float_to_act(res[u].x + v[u].x, p.bf16)) |
+                          (static_cast<uint32_t>(float_to_act(res[u].y + v[u].y, p.bf16)) << 16);
+                    o.y = static_cast<uint32_t>(float_to_act(res[u].z + v[u].z, p.bf16)) |
+                          (static_cast<uint32_t>(float_to_act(res[u].w + v[u].w, p.bf16)) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + static_cast<size_t>(trow[u]) * p.ldo + col) = o;
+                }
+            }
+        }
+    }
+}
+
 hipError_t launch_gemm_skinny(GemmDev& d, int epilogue, hipStream_t stream);
+hipError_t launch_gemm_mid(GemmDev& d, int epilogue, hipStream_t stream);
 
 }  // namespace qtale

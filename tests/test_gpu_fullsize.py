@@ -87,6 +87,13 @@ def test_llama7b_shaped_prefill_layer_three_bit(qt):
     _prefill_case(qt, dataclasses.replace(si.C2, bits=3), 8, 1024, 0.5, seq_to_check=2, seed=15)
 
 
+@pytest.mark.parametrize("ratio,threshold", [(0.5, None), (None, 0.4)])
+def test_llama7b_shaped_single_prompt_1x1024(qt, ratio, threshold):
+    # one 1024-token prompt: 512 (ratio) or about 640 (threshold) executed rows, the row counts at which the
+    # 4096-column linears run on 64-row tiles
+    _prefill_case(qt, si.C2, 1, 1024, ratio, seq_to_check=0, seed=16, threshold=threshold)
+
+
 def test_llama3_8b_shaped_gqa_prefill_layer_4x4096_ratio_06(qt):
     _prefill_case(qt, si.C4, 4, 4096, 0.6, seq_to_check=1, seed=12)
 

@@ -51,7 +51,8 @@ def test_quantize_rejects_bad_parameters(qt):
 
 @pytest.mark.parametrize("M,N,K,G", [(64, 256, 256, 32), (32, 256, 688, 32), (7, 688, 256, 32), (300, 416, 512, 128),
                                      (257, 1024, 1024, 128), (1, 96, 64, 64), (513, 4096, 264, 128),
-                                     (65, 4096, 1024, 128), (130, 416, 688, 32), (256, 1024, 512, 64)])
+                                     (65, 4096, 1024, 128), (130, 416, 688, 32), (256, 1024, 512, 64),
+                                     (700, 416, 688, 32), (1000, 96, 1096, 64), (1500, 200, 320, 128)])
 @pytest.mark.parametrize("bits", [4, 3, 2])
 def test_linear_w4a16_matches_oracle(qt, M, N, K, G, bits):
     W = _w(N, K, M + N + K)
@@ -92,7 +93,8 @@ def test_prepack_from_canonical_three_bit_codes(qt):
     assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
 
 
-@pytest.mark.parametrize("M,I,K,G", [(64, 688, 256, 32), (200, 352, 512, 128), (5, 64, 128, 64)])
+@pytest.mark.parametrize("M,I,K,G", [(64, 688, 256, 32), (200, 352, 512, 128), (5, 64, 128, 64),
+                                     (600, 352, 688, 32), (300, 1000, 136, 64), (1100, 96, 448, 128)])
 @pytest.mark.parametrize("bits", [4, 3, 2])
 def test_swiglu_w4a16_matches_oracle(qt, M, I, K, G, bits):
     Wg, Wu = _w(I, K, 1, 0.05), _w(I, K, 2, 0.05)
@@ -183,13 +185,13 @@ def test_mlp_router_scores_are_bit_exact(qt, T, H, R, dtype):
 
 
 def test_linear_random_shape_sweep(qt):
-    # 40 seeded shapes across the dispatch regimes (few rows / 64-row chunks / 128-row tiles), ragged K, output
+    # 40 seeded shapes across the dispatch regimes (few rows / 64-row chunks / 64-row tiles / 128-row tiles), ragged K, output
     # widths that are not multiples of the 32-column fragment, all code widths and group sizes
     rng = np.random.default_rng(2024)
     for case in range(40):
         bits = int(rng.choice([4, 3, 2]))
         G = int(rng.choice([32, 64, 128]))
-        M = int(rng.choice([1, 3, 17, 31, 33, 64, 65, 100, 129, 200, 256, 257, 300, 520]))
+        M = int(rng.choice([1, 3, 17, 31, 33, 64, 65, 100, 129, 200, 256, 257, 300, 520, 777, 1290]))
         N = 8 * int(rng.integers(1, 90))
         K = 8 * int(rng.integers(2, 140))
         g = torch.Generator().manual_seed(1000 + case)
@@ -210,7 +212,7 @@ def test_swiglu_random_shape_sweep(qt):
     for case in range(16):
         bits = int(rng.choice([4, 3, 2]))
         G = int(rng.choice([32, 64, 128]))
-        M = int(rng.choice([1, 30, 64, 70, 190, 256, 300]))
+        M = int(rng.choice([1, 30, 64, 70, 190, 256, 300, 650, 1300]))
         I = 8 * int(rng.integers(1, 120))
         K = 8 * int(rng.integers(2, 100))
         g = torch.Generator().manual_seed(2000 + case)

@@ -76,6 +76,14 @@ def test_layer_spans_several_row_tiles(qt):
     _check_layer(qt, shape, 700, [300, 400], "ratio", 0.8, seed=2, std=0.08)
 
 
+@pytest.mark.parametrize("bits,mode,val", [(4, "threshold", 0.5), (3, "ratio", 0.7), (2, "threshold", 0.45)])
+def test_layer_with_a_few_hundred_executed_rows(qt, bits, mode, val):
+    # 300-800 executed rows and narrow outputs: the 64-row-tile GEMM with all four epilogues, in threshold mode
+    # with the row count known only on the device; SwiGLU width 688 makes the down-proj K ragged
+    shape = si.LayerShape(256, 4, 4, 64, 688, bits, 32, "fp16")
+    _check_layer(qt, shape, 1100, [500, 600], mode, val, seed=30 + bits, std=0.08, starts=[0, 11])
+
+
 def test_layer_group64(qt):
     shape = si.LayerShape(256, 2, 1, 128, 512, 4, 64, "bf16")
     _check_layer(qt, shape, 150, [150], "threshold", 0.45, seed=3, std=0.08)
