@@ -179,6 +179,27 @@ def test_random_cache_scenarios(qt):
         _cache_case(qt, shape, lens, old, old, max(cap, 1), 300 + case, float(rng.choice([0.3, 0.5, 0.8, 1.0])))
 
 
+def test_random_prefill_layer_configurations(qt):
+    # seeded prefill layers across the GEMM dispatch regimes (a handful to ~1400 executed rows), both control
+    # modes, ragged sequence mixes (also empty ones), every code width, group size and stream dtype
+    rng = np.random.default_rng(4242)
+    for case in range(12):
+        nkv = int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([64, 128]))
+        nh = nkv * int(rng.choice([1, 2, 4]))
+        H = int(rng.choice([128, 256, 384]))
+        shape = si.LayerShape(H, nh, nkv, d, 8 * int(rng.integers(8, 90)), int(rng.choice([4, 3, 2])),
+                              int(rng.choice([32, 64, 128])), str(rng.choice(["fp16", "bf16"])))
+        B = int(rng.integers(1, 5))
+        T = int(rng.choice([40, 300, 700, 1100, 1500]))
+        cuts = np.sort(rng.integers(0, T + 1, size=B - 1))
+        lens = [int(v) for v in np.diff(np.concatenate([[0], cuts, [T]]))]
+        starts = [int(v) for v in rng.integers(0, 30, size=B)]
+        mode = str(rng.choice(["ratio", "threshold"]))
+        val = float(rng.choice([0.3, 0.6, 0.9, 1.0])) if mode == "ratio" else float(rng.choice([0.35, 0.5]))
+        _check_layer(qt, shape, T, lens, mode, val, seed=500 + case, std=0.08, starts=starts)
+
+
 def test_decode_step_with_cache(qt):
     # one new token per sequence against cached context; skipped tokens append nothing
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "fp16")
