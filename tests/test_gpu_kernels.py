@@ -137,6 +137,33 @@ def test_router_and_selection_are_bit_exact(qt, T, H, dtype):
         assert np.array_equal(cu.cpu().numpy(), cu_ref)
 
 
+def test_selection_beyond_the_on_chip_caches(qt):
+    # 40000 tokens in 3000 sequences: more keys and more sequence offsets than the selection kernel keeps in LDS
+    T, H, B = 40000, 64, 3000
+    shape = si.LayerShape(H, 1, 1, 64, 64, 4, 32, "bf16")
+    x = si.hidden_states(shape, T, 5)
+    w = si.router_weight(shape, 0, 5)
+    z_ref = orc.router_scores(x.to(torch.float64).numpy(), w.numpy(), -0.05)
+    rng = np.random.default_rng(5)
+    cuts = np.sort(rng.integers(0, T + 1, size=B - 1))
+    offs = torch.from_numpy(np.concatenate([[0], cuts, [T]]).astype(np.int32))
+    ctx = qt.Context()
+    for mode, val in [("ratio", 0.37), ("ratio", 1.0), ("threshold", 0.5), ("threshold", 0.31)]:
+        if mode == "ratio":
+            qt.qtale_set_exec_ratio(ctx, val)
+            want = orc.select_ratio(z_ref, val)
+        else:
+            qt.qtale_set_threshold(ctx, val)
+            want = orc.select_threshold(z_ref, val)
+        z, idx, cnt, cu = qt.qtale_router_select(ctx, x.cuda(), w.cuda(), -0.05, offs.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(z.cpu().numpy().view(np.uint32), z_ref.view(np.uint32))
+        k = int(cnt.item())
+        assert k == len(want), (mode, val)
+        assert np.array_equal(idx[:k].cpu().numpy(), want)
+        assert np.array_equal(cu.cpu().numpy(), np.searchsorted(want, offs.numpy(), side="left"))
+
+
 def test_selection_ties_go_to_lower_index(qt):
     # identical rows give identical scores: ties must be resolved by token index
     shape = si.LayerShape(64, 1, 1, 64, 64, 4, 32, "fp16")
