@@ -401,6 +401,34 @@ def main():
             single["by_exec_ratio"]["%.1f" % r] = {"tokens_per_s": S1 / dt1, "ms_per_step": dt1 * 1e3}
         qt.qtale_set_exec_ratio(ctx, args.ratio)
         del xs, ws1
+    # what the box itself delivers, for scale: a plain device copy and the vendor library's dense fp16 GEMM of
+    # the gate/up shape on random data (neither is part of the path)
+    ceilings = None
+    if not args.no_sweep:
+        src = torch.randn(256 * 1024 * 1024 // 4, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        copy_gbps = 10 * 2 * src.numel() * 4 / (time.perf_counter() - t0) / 1e9
+        del src, dst
+        a16 = torch.randn(k_exec, H, device=dev, dtype=torch.float16)
+        w16 = torch.randn(2 * I, H, device=dev, dtype=torch.float16) * 0.02
+        for _ in range(3):
+            torch.matmul(a16, w16.t())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            torch.matmul(a16, w16.t())
+        torch.cuda.synchronize()
+        lib_tflops = 10 * gu_flops / (time.perf_counter() - t0) / 1e12
+        del a16, w16
+        ceilings = {"device_copy_256MiB_GBps_read_plus_write": copy_gbps,
+                    "vendor_fp16_gemm_same_shape_TFLOPs": lib_tflops,
+                    "note": "torch copy_ and torch.matmul (fp16 x fp16, random data) on this GPU, M=%d N=%d K=%d" % (k_exec, 2 * I, H)}
     int3 = None
     if not args.no_int3:
         int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode, layers)
@@ -426,6 +454,7 @@ def main():
         "threshold_mode": threshold,
         "mlp_router": mlp,
         "single_prompt": single,
+        "box_ceilings": ceilings,
         "decode": decode,
         "int3": int3,
     }
