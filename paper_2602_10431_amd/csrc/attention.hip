@@ -14,6 +14,8 @@
 //     its way into LDS.
 //   * decode: one workgroup per (executed row, kv head); lanes stream K and V rows with 16-byte loads,
 //     16 (or 8) lanes per key, online softmax per lane group, merged at the end.  Bandwidth-bound.
+#include <algorithm>
+
 #include "qtale_dev.h"
 #include "qtale_kernels.h"
 
@@ -37,6 +39,8 @@ struct AttnDev {
     const int32_t* kv_old;
     int cap;
     float scale_log2;            // log2(e) / sqrt(d)
+    float* part;                 // decode, split keys: [row][head][split][D + 2] fp32 (numerators, maximum, denominator)
+    int n_split;                 // key ranges per (row, kv head); 1 = no split
 };
 
 template <int D>
@@ -305,7 +309,11 @@ attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int4* __restrict__
 }
 
 // Decode-style attention: workgroup = (executed row, kv head); REP query heads share the kv head.
-template <int D, int REP>
+// SPLIT: with few rows there are fewer workgroups than the chip needs to saturate HBM (8 rows x 32 kv heads is
+// one workgroup per CU: 4.1 TB/s against 6.0 with eight per CU), so the keys of a (row, kv head) are cut into
+// n_split contiguous ranges (multiples of the 64- or 128-key step) that separate workgroups stream; each writes
+// its unnormalised sums with their maximum and denominator, and attn_merge_kernel combines the ranges in order.
+template <int D, int REP, bool SPLIT>
 __global__ void __launch_bounds__(256)
 attn_decode_kernel(AttnDev p) {
     constexpr int LPK = D / 8;            // lanes per key (each lane owns 8 of the D columns)
@@ -352,6 +360,13 @@ attn_decode_kernel(AttnDev p) {
     }
 
     const int step = 4 * KPW;             // keys per workgroup step
+    int key_lo = 0, key_hi = n_keys;      // this workgroup's key range
+    if (SPLIT) {
+        const int gran = UNR * step;
+        const int per = ((n_keys + p.n_split - 1) / p.n_split + gran - 1) / gran * gran;
+        key_lo = min(static_cast<int>(blockIdx.z) * per, n_keys);
+        key_hi = min(key_lo + per, n_keys);
+    }
     // The keys and values of the next step are requested before the current step is consumed, so the memory
     // pipe never drains while the lanes do their dot products and exponentials (keys past the end are clamped
     // to the last one and masked).
@@ -360,19 +375,19 @@ attn_decode_kernel(AttnDev p) {
         const int k0 = kb + wave * KPW + slot;
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int kc = min(k0 + u * step, n_keys - 1);
+            const int kc = min(k0 + u * step, n_keys - 1);      // n_keys >= 1: always a valid row
             kn[u] = *reinterpret_cast<const half8_t*>(kbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
             vn[u] = *reinterpret_cast<const half8_t*>(vbase + static_cast<size_t>(kc) * kv_stride + sub * 8);
         }
     };
-    fetch(0);
-    for (int kb = 0; kb < n_keys; kb += UNR * step) {          // trip count is uniform over the workgroup
+    fetch(key_lo);
+    for (int kb = key_lo; kb < key_hi; kb += UNR * step) {     // trip count is uniform over the workgroup
         const int k0 = kb + wave * KPW + slot;
         half8_t kv[UNR], vv[UNR];
         bool ok[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            ok[u] = k0 + u * step < n_keys;
+            ok[u] = k0 + u * step < key_hi;
             kv[u] = kn[u];
             vv[u] = vn[u];
         }
@@ -444,20 +459,72 @@ attn_decode_kernel(AttnDev p) {
             num += sm[w][r][e] * a;
             den += sm[w][r][D + 1] * a;
         }
-        p.out[static_cast<size_t>(i) * (p.nh * D) + (hk * REP + r) * D + e] = static_cast<half_t>(num / den);
+        if (SPLIT) {
+            // an empty range leaves num = 0, den = 0 and the maximum at its initial value: it drops out of the merge
+            float* dst = p.part + ((static_cast<size_t>(i) * p.nh + hk * REP + r) * p.n_split + blockIdx.z) * (D + 2);
+            dst[e] = num;
+            if (e == 0) { dst[D] = mn; dst[D + 1] = den; }
+        } else {
+            p.out[static_cast<size_t>(i) * (p.nh * D) + (hk * REP + r) * D + e] = static_cast<half_t>(num / den);
+        }
     }
+}
+
+// Combines the key ranges of the split decode kernel: out = sum_s num_s 2^(m_s - m) / sum_s den_s 2^(m_s - m),
+// ranges taken in order.  One workgroup per (row, 256 / D heads).
+template <int D>
+__global__ void __launch_bounds__(256)
+attn_merge_kernel(AttnDev p) {
+    const int i = blockIdx.y;
+    if (i >= *p.count) return;
+    const int head = blockIdx.x * (256 / D) + threadIdx.x / D;
+    const int e = threadIdx.x % D;
+    if (head >= p.nh) return;
+    const float* src = p.part + (static_cast<size_t>(i) * p.nh + head) * p.n_split * (D + 2);
+    float mn = kNegBig;
+    for (int s = 0; s < p.n_split; ++s) mn = fmaxf(mn, src[s * (D + 2) + D]);
+    float num = 0.0f, den = 0.0f;
+    for (int s = 0; s < p.n_split; ++s) {
+        const float a = exp2f(src[s * (D + 2) + D] - mn);
+        num += src[s * (D + 2) + e] * a;
+        den += src[s * (D + 2) + D + 1] * a;
+    }
+    p.out[static_cast<size_t>(i) * (p.nh * D) + head * D + e] = static_cast<half_t>(num / den);
+}
+
+// CUs of the current device (queried once per device).
+static int attn_cus() {
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+template <int D, bool SPLIT>
+static hipError_t launch_decode_rep(const AttnDev& d, int rep, int rows, int nkv, hipStream_t stream) {
+    const dim3 grid(nkv, rows, SPLIT ? d.n_split : 1), block(256);
+    switch (rep) {
+        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1, SPLIT>), grid, block, 0, stream, d); break;
+        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2, SPLIT>), grid, block, 0, stream, d); break;
+        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4, SPLIT>), grid, block, 0, stream, d); break;
+        case 8: hipLaunchKernelGGL((attn_decode_kernel<D, 8, SPLIT>), grid, block, 0, stream, d); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_decode_d(const AttnDev& d, int rep, int rows, int nkv, hipStream_t stream) {
-    const dim3 grid(nkv, rows), block(256);
-    switch (rep) {
-        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, block, 0, stream, d); break;
-        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, block, 0, stream, d); break;
-        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4>), grid, block, 0, stream, d); break;
-        case 8: hipLaunchKernelGGL((attn_decode_kernel<D, 8>), grid, block, 0, stream, d); break;
-        default: return hipErrorInvalidValue;
-    }
+    if (d.n_split <= 1) return launch_decode_rep<D, false>(d, rep, rows, nkv, stream);
+    hipError_t e = launch_decode_rep<D, true>(d, rep, rows, nkv, stream);
+    if (e != hipSuccess) return e;
+    const dim3 grid((d.nh * D + 255) / 256, rows), block(256);
+    hipLaunchKernelGGL(attn_merge_kernel<D>, grid, block, 0, stream, d);
     return hipGetLastError();
 }
 
@@ -482,6 +549,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
     const int rep = a.nh / a.nkv;
     const bool decode_style = a.k_cache != nullptr && a.T <= 4 * a.B && (rep == 1 || rep == 2 || rep == 4 || rep == 8);
     if (decode_style) {
+        // Few rows: cut the keys so that about four workgroups per CU stream the cache (needs the partial buffer
+        // and pays one more launch, so only where the cache is long enough for the stream to matter).
+        d.n_split = 1;
+        d.part = a.partials;
+        const int wgs = a.max_rows * a.nkv;
+        if (a.partials && a.max_rows <= kAttnSplitRows && a.cap >= 1024 && wgs < 2 * attn_cus())
+            d.n_split = std::min(kAttnSplitMax, (4 * attn_cus() + wgs - 1) / wgs);
         return a.d == 128 ? launch_decode_d<128>(d, rep, a.max_rows, a.nkv, stream)
                           : launch_decode_d<64>(d, rep, a.max_rows, a.nkv, stream);
     }

@@ -45,6 +45,7 @@ struct Workspace {
     void* attn;            // [T][nh d] fp16
     float* h;              // [T][H] fp32
     void* act;             // [T][I] fp16
+    float* attn_part;      // [min(T, kAttnSplitRows)][nh][kAttnSplitMax][d + 2] fp32: key-range partials of decode attention
     size_t total;
 };
 
@@ -70,6 +71,8 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
     w.attn = take(Tz * c->n_heads * c->head_dim * 2);
     w.h = reinterpret_cast<float*>(take(Tz * c->hidden * 4));
     w.act = take(Tz * c->inter * 2);
+    w.attn_part = reinterpret_cast<float*>(take(static_cast<size_t>(T < kAttnSplitRows ? T : kAttnSplitRows) * c->n_heads *
+                                                kAttnSplitMax * (c->head_dim + 2) * 4));
     w.total = off;
     return w;
 }
@@ -238,7 +241,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         a.qkv = ws.qkv; a.out = ws.attn; a.nh = nh; a.nkv = nkv; a.d = d; a.count = count; a.max_rows = M_max;
         a.B = B; a.cu_exec = ws.cu_exec; a.row_seq = ws.row_seq;
         if (kv) { a.k_cache = kv->k_cache; a.v_cache = kv->v_cache; a.cap = kv->cap; }
-        a.kv_old = ws.kv_old; a.T = T; a.items = ws.items; a.n_items = ws.scalars + 1;
+        a.kv_old = ws.kv_old; a.T = T; a.items = ws.items; a.n_items = ws.scalars + 1; a.partials = ws.attn_part;
         HIP_TRY(launch_attention(a, stream));
     }
     {

@@ -115,8 +115,12 @@ struct AttnArgs {
     int T;                     // tokens in the call
     void* items;               // scratch: (max_rows / kAttnBQ + B + 1) x int4 work list of the prefill kernel, 16-byte aligned
     int32_t* n_items;          // scratch [1]
+    float* partials;           // scratch (nullable): min(max_rows, kAttnSplitRows) x nh x kAttnSplitMax x (d + 2) fp32,
+                               // lets the decode kernel cut long caches into key ranges when there are few rows
 };
 constexpr int kAttnBQ = 128;   // executed rows per prefill-attention workgroup
+constexpr int kAttnSplitRows = 128;   // decode attention splits the keys only up to this many rows
+constexpr int kAttnSplitMax = 8;      // and into at most this many ranges
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace qtale

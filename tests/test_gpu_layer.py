@@ -200,6 +200,17 @@ def test_random_prefill_layer_configurations(qt):
         _check_layer(qt, shape, T, lens, mode, val, seed=500 + case, std=0.08, starts=starts)
 
 
+@pytest.mark.parametrize("nh,nkv,d", [(4, 4, 64), (8, 2, 128), (4, 1, 128)])
+def test_decode_attention_with_split_key_ranges(qt, nh, nkv, d):
+    # few rows against long caches: the decode attention kernel cuts each (row, kv head) into key ranges that
+    # separate workgroups stream and a merge kernel combines; one sequence is so short that most of its ranges
+    # are empty, one call has several new rows per sequence, one cache is exactly full after the append
+    shape = si.LayerShape(256, nh, nkv, d, 512, 4, 32, "fp16")
+    _cache_case(qt, shape, [1, 1, 1], [1500, 1030, 7], [1500, 1030, 7], 1600, 61, 1.0)
+    _cache_case(qt, shape, [3, 2, 1, 2], [1200, 64, 1999, 0], [1200, 64, 1999, 0], 2000, 62, 1.0)
+    _cache_case(qt, shape, [1] * 6, [1023, 1100, 1, 640, 1290, 300], [1023, 1100, 1, 640, 1290, 300], 1300, 63, 0.67)
+
+
 def test_decode_step_with_cache(qt):
     # one new token per sequence against cached context; skipped tokens append nothing
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "fp16")
