@@ -15,6 +15,7 @@
 //   * decode: one workgroup per (executed row, kv head); lanes stream K and V rows with 16-byte loads,
 //     16 (or 8) lanes per key, online softmax per lane group, merged at the end.  Bandwidth-bound.
 #include <algorithm>
+#include <type_traits>
 
 #include "qtale_dev.h"
 #include "qtale_kernels.h"
@@ -308,6 +309,24 @@ attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int4* __restrict__
     if (threadIdx.x == 0) *n_items = used;
 }
 
+// Sum over the LPK (8 or 16) adjacent lanes that share a key, left in every one of them.  Data-parallel-primitive
+// modifiers on the adds (quad permutes, then mirror within 8 and within 16 lanes: after the quad steps the
+// lanes of a quad hold equal values, so a mirror exchanges whole quads / halves) instead of cross-lane moves
+// through the LDS crossbar: the dot products of a decode step need 4 such sums per key and query head.
+template <int LPK>
+__device__ __forceinline__ float key_group_sum(float x) {
+    static_assert(LPK == 8 || LPK == 16, "8 or 16 lanes per key");
+    auto step = [](float v, auto ctrl) {
+        const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value, 0xf, 0xf, true);
+        return v + __builtin_bit_cast(float, moved);
+    };
+    x = step(x, std::integral_constant<int, 0xB1>{});       // quad_perm [1,0,3,2]
+    x = step(x, std::integral_constant<int, 0x4E>{});       // quad_perm [2,3,0,1]
+    x = step(x, std::integral_constant<int, 0x141>{});      // row_half_mirror
+    if (LPK == 16) x = step(x, std::integral_constant<int, 0x140>{});   // row_mirror
+    return x;
+}
+
 // Decode-style attention: workgroup = (executed row, kv head); REP query heads share the kv head.
 // SPLIT: with few rows there are fewer workgroups than the chip needs to saturate HBM (8 rows x 32 kv heads is
 // one workgroup per CU: 4.1 TB/s against 6.0 with eight per CU), so the keys of a (row, kv head) are cut into
@@ -401,8 +420,7 @@ attn_decode_kernel(AttnDev p) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc = fmaf(q[r][e], static_cast<float>(kv[u][e]), acc);
-#pragma unroll
-                for (int off = LPK >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                acc = key_group_sum<LPK>(acc);
                 s[u] = ok[u] ? acc : kNegBig;
                 mx = fmaxf(mx, s[u]);
             }
