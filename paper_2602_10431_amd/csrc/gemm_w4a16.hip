@@ -18,6 +18,7 @@
 //     of x into an fp32 h (o-proj), SiLU(gate)*up (MLP), residual add + scatter back into x (down-proj).
 //     The accumulators are transposed through LDS so that every global access is row-contiguous.
 #include <algorithm>
+#include <type_traits>
 
 #include "gemm_common.h"
 
@@ -127,8 +128,13 @@ gemm_w4a16_kernel(GemmDev p) {
         for (int it = 0; it < A_LOADS; ++it) *reinterpret_cast<u32x4_t*>(&As[buf][a_dst[it]]) = areg[it];
     };
 
-    typename WB::Tile bq[2][FN];         // packed codes of the current / next k-tile (ping-pong)
-    uint32_t bsz[2][FN][GPT];       // their scale|zero words
+    // Packed codes and scale|zero words of the k-tiles in flight.  One-tile-per-workgroup form: a ring of three
+    // slots (tile t in slot t%3, the loads of tile t+2 are issued at the start of tile t, the k-loop is unrolled
+    // by three so that slots are compile-time).  Persistent form: current / next (ping-pong with a copy).
+    constexpr bool RING = !PERSIST && GPT == 1;      // (two groups per k-tile: the third slot would not fit the register file)
+    constexpr int NB = RING ? 3 : 2;
+    typename WB::Tile bq[NB][FN];
+    uint32_t bsz[NB][FN][GPT];
     auto load_b = [&](int kt, typename WB::Tile* q, uint32_t (*sz)[GPT]) {
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) {
@@ -144,8 +150,10 @@ gemm_w4a16_kernel(GemmDev p) {
     const int a_row0 = (wm * FM * 32 + l32) * kLdsStride + lhi * 8;
 
     // Pipeline (per wave, MFMAs never stop at a tile boundary):
-    //   tile t is computed from LDS buffer t%3 and the codes in bq[0] (bq[1] receives tile t+1);
-    //   start of tile t : issue the B loads of tile t+1;
+    //   tile t is computed from LDS buffer t%3 and the codes of its ring slot;
+    //   start of tile t : issue the B loads of tile t+2 (ring form; tile t+1 in the ping-pong form): weights come
+    //                     from L2/HBM, and a prefetch distance of one tile left part of that latency exposed even
+    //                     with two workgroups per CU (measured +1.5 % at 4096 rows, +3 % at 512);
     //   after k-step 0  : park the A registers of tile t+1 (loaded one tile ago) in buffer (t+1)%3, issue
     //                     the A loads of tile t+2, barrier (buffer (t+1)%3 becomes visible; three buffers
     //                     make the write safe against waves still reading tile t-1);
@@ -160,6 +168,7 @@ gemm_w4a16_kernel(GemmDev p) {
     const int last = p.KT - 1;
     load_a(0);
     load_b(0, bq[0], bsz[0]);
+    if (RING) load_b(min(1, last), bq[1], bsz[1]);
     store_a(0);
     // Drain the prologue loads here: a load still pending at the loop header would make the compiler
     // place its vmcnt wait inside the loop, where it would also wait for the prefetches just issued.
@@ -171,17 +180,19 @@ gemm_w4a16_kernel(GemmDev p) {
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) a[0][fm] = *reinterpret_cast<const half8_t*>(&As[0][a_row0 + fm * 32 * kLdsStride]);
     int buf = 0;
-    for (int kt = 0; kt < p.KT; ++kt) {
+    // one k-tile: weights from slot S, the prefetch (tile kt + DIST) goes to slot P
+    auto k_tile = [&](int kt, auto s_c, auto p_c, auto dist_c) {
+        constexpr int S = decltype(s_c)::value, P = decltype(p_c)::value, DIST = decltype(dist_c)::value;
         const int nbuf = buf == NBUF - 1 ? 0 : buf + 1;
-        load_b(min(kt + 1, last), bq[1], bsz[1]);
+        load_b(min(kt + DIST, last), bq[P], bsz[P]);
         typename WB::SZ sz[FN][GPT];
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) sz[fn][g] = WB::expand(bsz[0][fn][g]);
+            for (int g = 0; g < GPT; ++g) sz[fn][g] = WB::expand(bsz[S][fn][g]);
         const half_t* Ab = &As[buf][a_row0];
         const half_t* An = &As[nbuf][a_row0];
-        half8_t bcur = WB::dequant(bq[0][0], 0, sz[0][0], magic);
+        half8_t bcur = WB::dequant(bq[S][0], 0, sz[0][0], magic);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j == 1) {
@@ -198,7 +209,7 @@ gemm_w4a16_kernel(GemmDev p) {
                 const int jn = fn + 1 < FN ? j : j + 1;
                 half8_t bnext = bcur;
                 if (jn < 4) {
-                    bnext = WB::dequant(bq[0][fnn], jn, sz[fnn][GPT == 2 ? (jn >> 1) : 0], magic);
+                    bnext = WB::dequant(bq[S][fnn], jn, sz[fnn][GPT == 2 ? (jn >> 1) : 0], magic);
                 }
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
@@ -206,13 +217,32 @@ gemm_w4a16_kernel(GemmDev p) {
                 bcur = bnext;
             }
         }
-#pragma unroll
-        for (int fn = 0; fn < FN; ++fn) {
-            bq[0][fn] = bq[1][fn];
-#pragma unroll
-            for (int g = 0; g < GPT; ++g) bsz[0][fn][g] = bsz[1][fn][g];
-        }
         buf = nbuf;
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    if constexpr (RING) {
+        int kt = 0;
+        for (; kt + 3 <= p.KT; kt += 3) {
+            k_tile(kt, I0{}, I2{}, I2{});
+            k_tile(kt + 1, I1{}, I0{}, I2{});
+            k_tile(kt + 2, I2{}, I1{}, I2{});
+        }
+        if (kt < p.KT) {                           // one or two tiles left, in slots 0 and 1
+            k_tile(kt, I0{}, I2{}, I2{});
+            if (kt + 1 < p.KT) k_tile(kt + 1, I1{}, I0{}, I2{});
+        }
+    } else {
+        for (int kt = 0; kt < p.KT; ++kt) {
+            k_tile(kt, I0{}, I1{}, I1{});
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                bq[0][fn] = bq[1][fn];
+#pragma unroll
+                for (int g = 0; g < GPT; ++g) bsz[0][fn][g] = bsz[1][fn][g];
+            }
+        }
     }
     __syncthreads();     // every wave is done with the A tiles: the epilogue reuses the LDS
 
