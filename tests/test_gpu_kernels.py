@@ -211,6 +211,37 @@ def test_mlp_router_scores_are_bit_exact(qt, T, H, R, dtype):
     assert np.array_equal(z.cpu().numpy().view(np.uint32), want.view(np.uint32))
 
 
+@pytest.mark.parametrize("K,G,bits", [(40, 32, 4), (72, 64, 3), (264, 128, 2), (320, 32, 3), (384, 128, 4), (456, 64, 2)])
+def test_large_tile_gemm_short_and_ragged_k(qt, K, G, bits):
+    # 2600 rows x 2048 columns is past the 64-row-tile regime, so these run the 128 x 256 tiles: one to eight
+    # k-tiles (every remainder of the three-slot weight ring), K not a multiple of 64, every code width
+    M, N = 2600, 2048
+    W = _w(N, K, K)
+    A = torch.randn(M, K, generator=torch.Generator().manual_seed(K)).to(torch.float16)
+    ql = qt.qtale_quantize(W.cuda(), bits, G)
+    out = qt.qtale_linear_w4a16(ql, A.cuda())
+    torch.cuda.synchronize()
+    codes, s, z = orc.quantize_rtn(W.numpy(), bits, G)
+    want = A.to(torch.float64).numpy() @ orc.dequantize(codes, s, z, G).T
+    assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
+
+
+@pytest.mark.parametrize("K,G,bits", [(136, 64, 4), (320, 32, 3)])
+def test_large_tile_swiglu_short_and_ragged_k(qt, K, G, bits):
+    M, I = 2600, 2048
+    g = torch.Generator().manual_seed(K)
+    Wg, Wu = torch.randn(I, K, generator=g) * 0.05, torch.randn(I, K, generator=g) * 0.05
+    A = torch.randn(M, K, generator=g).to(torch.float16)
+    qg, qu = qt.qtale_quantize(Wg.cuda(), bits, G), qt.qtale_quantize(Wu.cuda(), bits, G)
+    out = qt.qtale_swiglu_w4a16(qg, qu, A.cuda())
+    torch.cuda.synchronize()
+    A64 = A.to(torch.float64).numpy()
+    dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), bits, G), G)
+    du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), bits, G), G)
+    want = orc.silu(A64 @ dg.T) * (A64 @ du.T)
+    assert orc.parity_error(out.cpu().to(torch.float64).numpy(), want) <= TOL
+
+
 def test_linear_random_shape_sweep(qt):
     # 40 seeded shapes across the dispatch regimes (few rows / 64-row chunks / 64-row tiles / 128-row tiles), ragged K, output
     # widths that are not multiples of the 32-column fragment, all code widths and group sizes

@@ -84,6 +84,14 @@ def test_layer_with_a_few_hundred_executed_rows(qt, bits, mode, val):
     _check_layer(qt, shape, 1100, [500, 600], mode, val, seed=30 + bits, std=0.08, starts=[0, 11])
 
 
+@pytest.mark.parametrize("mode,val", [("ratio", 1.0), ("threshold", 0.3)])
+def test_layer_on_large_tiles_with_ragged_down_proj(qt, mode, val):
+    # hidden 1024 and more than 5120 executed rows: every linear of the layer runs on the 128 x 256 tiles (ratio
+    # mode: one tile per workgroup; threshold mode: persistent workgroups), the down-proj with K = 1384
+    shape = si.LayerShape(1024, 8, 8, 128, 1384, 4, 128, "bf16")
+    _check_layer(qt, shape, 5600, [2700, 2900], mode, val, seed=40, std=0.04)
+
+
 def test_layer_group64(qt):
     shape = si.LayerShape(256, 2, 1, 128, 512, 4, 64, "bf16")
     _check_layer(qt, shape, 150, [150], "threshold", 0.45, seed=3, std=0.08)
