@@ -19,7 +19,9 @@ def _compile(src):
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "not a recognized feature" not in l)
-    if r.returncode != 0:
+    # the host pass can die ("fatal error: error in backend") while the driver still returns 0 and leaves an
+    # object without device code behind
+    if r.returncode != 0 or "error:" in err:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
     if err.strip():
         sys.stderr.write(err + "\n")
