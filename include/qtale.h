@@ -158,6 +158,22 @@ int qtale_layer_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_
                         const qtale_kv* kv, int32_t* sel_idx, int32_t* sel_count, float* scores,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): qtale_layer_forward with the workspace taken from an array inside the library instead
+ * of a caller buffer.  Same arguments, same kernels and bit-identical results; the call allocates and frees
+ * nothing.  The array is QTALE_STATIC_SCRATCH_BYTES large (enough for a decode step of 128 one-token sequences
+ * at hidden 5120 / 40 heads / SwiGLU 13824, or about 300 prefill tokens at hidden 4096 / SwiGLU 11008) and every
+ * GPU the library runs on holds one copy until the process ends.  A call whose workspace
+ * (qtale_workspace_bytes(cfg, T, B)) is larger returns QTALE_ERR_WORKSPACE_TOO_SMALL before any GPU work.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or threads) race;
+ * serialize them.  Returns QTALE_ERR_INVALID_ARG while per-kernel profiling is enabled. */
+#define QTALE_STATIC_SCRATCH_BYTES (40u << 20)
+size_t qtale_static_scratch_bytes(void);
+int qtale_layer_forward_static(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* w,
+                               void* x, int T, const int32_t* seq_offsets, int B, const int32_t* positions,
+                               const qtale_kv* kv, int32_t* sel_idx, int32_t* sel_count, float* scores,
+                               void* stream);
+
 /* n_layers layers in sequence with the context's single control value (one global knob, Sec. 3.4).
  *   layers       host array [n_layers]
  *   kv_per_layer host array [n_layers], nullable

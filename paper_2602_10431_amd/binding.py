@@ -24,7 +24,8 @@ EXPORTS = ["qtale_strerror", "qtale_create", "qtale_destroy", "qtale_set_exec_ra
            "qtale_workspace_bytes", "qtale_layer_forward", "qtale_stack_forward", "qtale_router_select",
            "qtale_linear_w4a16", "qtale_swiglu_w4a16", "qtale_profile_enable", "qtale_profile_read",
            "qtale_calibration_scratch_bytes", "qtale_calibrate_threshold_from_scores", "qtale_calibrate_threshold",
-           "qtale_graph_capture_stack", "qtale_graph_launch", "qtale_graph_destroy", "qtale_router_mlp_scores"]
+           "qtale_graph_capture_stack", "qtale_graph_launch", "qtale_graph_destroy", "qtale_router_mlp_scores",
+           "qtale_static_scratch_bytes", "qtale_layer_forward_static"]
 QTALE_THETA_GRID = 50
 
 
@@ -84,6 +85,10 @@ def load_library():
     lib.qtale_workspace_bytes.argtypes = [C.POINTER(qtale_layer_cfg), i, i]
     lib.qtale_layer_forward.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), vp, i, vp, i,
                                         vp, C.POINTER(qtale_kv), vp, vp, vp, vp, sz, vp]
+    lib.qtale_static_scratch_bytes.restype = sz
+    lib.qtale_static_scratch_bytes.argtypes = []
+    lib.qtale_layer_forward_static.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), vp, i, vp,
+                                               i, vp, C.POINTER(qtale_kv), vp, vp, vp, vp]
     lib.qtale_stack_forward.argtypes = [vp, C.POINTER(qtale_layer_cfg), C.POINTER(qtale_layer_weights), i, vp, i, vp,
                                         i, vp, C.POINTER(qtale_kv), vp, vp, vp, vp, vp, sz, vp]
     lib.qtale_router_select.argtypes = [vp, i, vp, i, i, vp, f, vp, i, vp, vp, vp, vp, vp]
@@ -105,7 +110,7 @@ def load_library():
     lib.qtale_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     for name in EXPORTS:
         if name not in ("qtale_strerror", "qtale_prepacked_bytes", "qtale_workspace_bytes",
-                        "qtale_calibration_scratch_bytes", "qtale_graph_destroy"):
+                        "qtale_calibration_scratch_bytes", "qtale_graph_destroy", "qtale_static_scratch_bytes"):
             getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -288,6 +293,23 @@ def qtale_layer_forward(ctx, cfg, weights, x, seq_offsets, positions, kv=None, s
         ctx._h, C.byref(cfg), C.byref(w), _ptr(x), T, _ptr(seq_offsets), B, _ptr(positions),
         C.byref(kvs) if kvs is not None else None, _ptr(sel_idx), _ptr(sel_count), _ptr(scores),
         _ptr(workspace), workspace.numel(), _stream()), "qtale_layer_forward")
+
+
+def qtale_static_scratch_bytes():
+    return load_library().qtale_static_scratch_bytes()
+
+
+def qtale_layer_forward_static(ctx, cfg, weights, x, seq_offsets, positions, kv=None, sel_idx=None, sel_count=None,
+                               scores=None):
+    """qtale_layer_forward on the library's own scratch array: the call allocates nothing."""
+    T = x.shape[0]
+    B = seq_offsets.numel() - 1
+    w = weights.c_struct()
+    kvs = kv.c_struct() if kv is not None else None
+    _check(load_library().qtale_layer_forward_static(
+        ctx._h, C.byref(cfg), C.byref(w), _ptr(x), T, _ptr(seq_offsets), B, _ptr(positions),
+        C.byref(kvs) if kvs is not None else None, _ptr(sel_idx), _ptr(sel_count), _ptr(scores), _stream()),
+        "qtale_layer_forward_static")
 
 
 class Stack:

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -433,6 +434,58 @@ int qtale_layer_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_
     if ((e = check_weights(cfg, w))) return e;
     if ((e = check_kv(kv))) return e;
     const Workspace ws = carve(cfg, T, B, workspace);
+    return layer_forward_impl(ctx, cfg, w, x, T, seq_offsets, B, positions, kv, sel_idx, sel_count, scores, ws,
+                              reinterpret_cast<hipStream_t>(stream));
+}
+
+// ---- layer forward on the library's own scratch array (for callers that cannot allocate) ------------------
+// The workspace of qtale_layer_forward lives in a file-scope device array instead of a caller buffer.  In host
+// code the array's name is only a handle: its device address is looked up once per device with
+// hipGetSymbolAddress (every GPU holds its own copy at its own address) and that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(QTALE_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (resolved on the first call per device).
+int static_scratch(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return QTALE_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0) return QTALE_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return QTALE_OK;
+}
+}  // namespace
+
+size_t qtale_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int qtale_layer_forward_static(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_layer_weights* w, void* x, int T,
+                               const int32_t* seq_offsets, int B, const int32_t* positions, const qtale_kv* kv,
+                               int32_t* sel_idx, int32_t* sel_count, float* scores, void* stream) {
+    if (!ctx) return QTALE_ERR_INVALID_ARG;
+    int e = check_cfg(cfg);
+    if (e) return e;
+    if (T < 0 || B < 0) return QTALE_ERR_INVALID_ARG;
+    if (T == 0) return QTALE_OK;
+    if (!x || !seq_offsets || !positions || B == 0) return QTALE_ERR_INVALID_ARG;
+    if (ctx->profiling) return QTALE_ERR_INVALID_ARG;          // the per-kernel timer creates events
+    if (carve(cfg, T, B, nullptr).total > kStaticScratchBytes) return QTALE_ERR_WORKSPACE_TOO_SMALL;
+    if ((e = check_weights(cfg, w))) return e;
+    if ((e = check_kv(kv))) return e;
+    void* base = nullptr;
+    if ((e = static_scratch(&base))) return e;
+    // Nothing in the workspace has to start at zero: every kernel of the layer writes what it later reads.
+    const Workspace ws = carve(cfg, T, B, base);
     return layer_forward_impl(ctx, cfg, w, x, T, seq_offsets, B, positions, kv, sel_idx, sel_count, scores, ws,
                               reinterpret_cast<hipStream_t>(stream));
 }

@@ -131,3 +131,25 @@ def test_calibration_argument_validation_needs_no_gpu(qt):
     mode, value = qt.qtale_get_control(ctx)                      # failed calls leave the control untouched
     assert mode == qt.QTALE_MODE_RATIO and value == 1.0
 
+
+
+def test_static_scratch_entry_validates_before_any_gpu_work(qt):
+    lib = qt.load_library()
+    ctx = qt.Context()
+    fake = C.c_void_p(256)
+    w = qt.qtale_layer_weights()
+    assert qt.qtale_static_scratch_bytes() == 40 << 20
+    big = qt.make_cfg(4096, 32, 32, 128, 11008)
+    small = qt.make_cfg(256, 4, 4, 64, 688, group=32, act_dtype="fp16")
+
+    def call(cfg_, T, B=1, x=fake):
+        return lib.qtale_layer_forward_static(ctx._h, C.byref(cfg_), C.byref(w), x, T, fake, B, fake, None, None, None,
+                                              None, None)
+
+    assert qt.qtale_workspace_bytes(big, 4096, 1) > qt.qtale_static_scratch_bytes()
+    assert call(big, 4096) == -4                                 # beyond the array: rejected, nothing launched
+    assert call(small, 8, x=None) == -1
+    assert call(small, -1) == -1
+    assert call(small, 0) == 0
+    assert call(small, 8) == -1                                  # fits, but the weights have no prepacked buffers
+    assert call(qt.make_cfg(256, 4, 4, 80, 688, group=32), 8) == -3
