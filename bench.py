@@ -23,8 +23,19 @@ HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
+def _blas_threads():
+    """Threads the NumPy BLAS pool will use (the oracle's matrix products run there)."""
+    try:
+        import threadpoolctl
+        n = [d["num_threads"] for d in threadpoolctl.threadpool_info() if d.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return os.cpu_count() or 1
+
+
 def cpu_baseline(shape, n_seq, seq_len, ratio, n_layers, reps=3):
-    """Times the CPU oracle (as it stands) on a bounded sample: layer 0 on the whole batch, `reps` batches."""
+    """Times the CPU oracle (as it stands) on a bounded sample: layer 0 on whole batches with the BLAS pool as
+    NumPy finds it, then the same layer on a quarter batch with the pool limited to one thread."""
     import numpy as np
     import torch
     import synth_inputs as si
@@ -43,15 +54,31 @@ def cpu_baseline(shape, n_seq, seq_len, ratio, n_layers, reps=3):
     T = n_seq * seq_len
     xs = [f64(si.hidden_states(shape, T, 0, extra=i)) for i in range(reps)]
     offs, pos = si.equal_sequences(n_seq, seq_len)
+    cores = _blas_threads()
     t0 = time.perf_counter()
     for x in xs:
         orc.layer_forward(x, p, cfg, offs.numpy(), pos.numpy(), "ratio", ratio)
     dt = (time.perf_counter() - t0) / reps
-    cores = torch.get_num_threads()
-    return {"value": T / (dt * n_layers), "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "oracle layer_forward (fp64 NumPy) on layer 0 and %d batches of %d x %d tokens at ratio %.2f: "
-                      "%.2f s per batch; stack rate extrapolated as tokens / (%d layers x layer time)"
-                      % (reps, n_seq, seq_len, ratio, dt, n_layers)}
+    out = {"value": T / (dt * n_layers), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+           "sample": "oracle layer_forward (fp64 NumPy, BLAS pool of %d threads) on layer 0 and %d batches of %d x %d "
+                     "tokens at ratio %.2f: %.2f s per batch; stack rate extrapolated as tokens / (%d layers x layer time)"
+                     % (cores, reps, n_seq, seq_len, ratio, dt, n_layers)}
+    # one core: the same layer on a quarter of the sequences, BLAS pool limited to a single thread
+    try:
+        import threadpoolctl
+        n1 = max(1, n_seq // 4)
+        o1, p1 = si.equal_sequences(n1, seq_len)
+        x1 = xs[0][:n1 * seq_len]
+        with threadpoolctl.threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            orc.layer_forward(x1, p, cfg, o1.numpy(), p1.numpy(), "ratio", ratio)
+            dt1 = time.perf_counter() - t0
+        out["one_core"] = {"value": n1 * seq_len / (dt1 * n_layers), "unit": "tokens/s", "cores": 1,
+                           "sample": "same layer on %d x %d tokens with the BLAS pool limited to 1 thread: %.2f s; "
+                                     "extrapolated to %d layers" % (n1, seq_len, dt1, n_layers)}
+    except Exception as e:      # threadpoolctl missing: report that instead of a number
+        out["one_core"] = {"value": None, "note": "threadpoolctl unavailable: %s" % e}
+    return out
 
 
 def recorded_traffic():
@@ -74,84 +101,166 @@ def recorded_traffic():
     return float(vals["traffic_bytes_per_launch"])
 
 
-def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=16, bits=4, ratios=(1.0, 0.8, 0.6, 0.4)):
-    """Secondary measurement (configs[2]): decode steps of the same stack, batch 64, 2048 cached
-    entries per sequence and layer (random fp16 K/V), execution ratio changed at run time."""
+def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=256, bits=4, ratios=(1.0, 0.8, 0.6, 0.4),
+                   base=None, kv_distinct=None, graph_steps=32, label="configs[2]"):
+    """Decode steps of a stack: batch B, ctx_len cached entries per sequence and layer (random fp16 K/V), `steps`
+    generated steps per ratio, execution ratio changed at run time (no requantization).  Every input of the timed
+    loops (hidden states, positions) is staged on the GPU beforehand: the loops contain library calls only.
+    kv_distinct: number of distinct per-layer K/V buffers; layers beyond it alias them round-robin (each layer keeps
+    its own length counters) - for stacks whose caches exceed HBM."""
+    import dataclasses
     dev = "cuda"
-    shape = si.LayerShape(4096, 32, 32, 128, 11008, bits, 128, "fp16")
+    base = base or si.C2
+    shape = dataclasses.replace(base, bits=bits, act_dtype="fp16")
     cfg = qt.cfg_from_shape(shape)
+    nkv, d = shape.n_kv_heads, shape.head_dim
     fp16_layers = []
     for lw in layers:                                  # same quantized weights, fp16 gains for an fp16 stream
         fp16_layers.append(qt.LayerWeights(lw.lin["q"], lw.lin["k"], lw.lin["v"], lw.lin["o"], lw.lin["gate"],
                                            lw.lin["up"], lw.lin["down"], lw.norm1.to(torch.float16),
                                            lw.norm2.to(torch.float16), lw.router_w, lw.router_b))
     cap = ctx_len + steps + 8
-    kvs = []
-    for l in range(L):
-        k = torch.randn(B, 32, cap, 128, device=dev, dtype=torch.float16)      # [B][kv heads][cap][head_dim]
-        v = torch.randn(B, 32, cap, 128, device=dev, dtype=torch.float16)
-        kvs.append(qt.KVCache(k, v, torch.full((B,), ctx_len, dtype=torch.int32, device=dev)))
+    n_buf = L if kv_distinct is None else min(L, kv_distinct)
+    bufs = []
+    for l in range(n_buf):
+        k = torch.randn(B, nkv, cap, d, device=dev, dtype=torch.float16)       # [B][kv heads][cap][head_dim]
+        v = torch.randn(B, nkv, cap, d, device=dev, dtype=torch.float16)
+        bufs.append((k, v))
+    kvs = [qt.KVCache(bufs[l % n_buf][0], bufs[l % n_buf][1], torch.full((B,), ctx_len, dtype=torch.int32, device=dev))
+           for l in range(L)]
     stack = qt.Stack(cfg, fp16_layers, kvs)
     offs = torch.arange(0, B + 1, dtype=torch.int32, device=dev)
     ws = qt.alloc_workspace(cfg, B, B, dev)
     ctx = qt.Context()
-    xs = [si.hidden_states(shape, B, 0, slot="x_step", extra=i, device=dev) for i in range(steps)]
+    n_x = min(steps, 16)                                # distinct hidden-state batches, reused round-robin
+    xs = [si.hidden_states(shape, B, 0, slot="x_step", extra=i, device=dev) for i in range(n_x)]
+    x_run = [torch.empty_like(xs[0]) for _ in range(steps)]
+    pos_run = [torch.full((B,), ctx_len + i, dtype=torch.int32, device=dev) for i in range(steps)]
+    H = shape.hidden
+    w_bytes = shape.params_per_layer() * bits // 8 + 4 * (shape.params_per_layer() // shape.group)
     res = {}
     for r in ratios:
         qt.qtale_set_exec_ratio(ctx, r)                 # runtime change: no requantization
         k_exec = int(float(torch.tensor(r, dtype=torch.float32)) * B + 0.5)
 
-        def run(profile):
+        def stage(n):
             for kv in kvs:
                 kv.kv_len.fill_(ctx_len)
+            for i in range(n):
+                x_run[i].copy_(xs[i % n_x])             # the stack updates x in place: fresh copies per step
             torch.cuda.synchronize()
+
+        def run(n, profile=False):
+            stage(n)
             qt.qtale_profile_enable(ctx, profile)
             t0 = time.perf_counter()
-            for i in range(steps):
-                pos = torch.full((B,), ctx_len + i, dtype=torch.int32, device=dev)
-                qt.qtale_stack_forward(ctx, stack, xs[i].clone(), offs, pos, workspace=ws)
+            for i in range(n):
+                qt.qtale_stack_forward(ctx, stack, x_run[i], offs, pos_run[i], workspace=ws)
             torch.cuda.synchronize()
             return time.perf_counter() - t0
 
-        def run_graph():
-            # the same steps replayed from one HIP graph: x and positions are rewritten in place
-            x_buf = torch.empty_like(xs[0])
-            pos_buf = torch.empty(B, dtype=torch.int32, device=dev)
-            for kv in kvs:
-                kv.kv_len.fill_(ctx_len)
-            graph = qt.StackGraph(ctx, stack, x_buf, offs, pos_buf, workspace=ws)
+        def run_graph(n):
+            # the same step replayed from one HIP graph (pointers baked in): the replay loop contains graph launches
+            # only, so x is whatever the previous replay left and the positions stay at ctx_len (cache lengths still
+            # advance on the device); same kernels and shapes as the eager steps
+            stage(1)
+            graph = qt.StackGraph(ctx, stack, x_run[0], offs, pos_run[0], workspace=ws)
             best = None
             for _ in range(2):
-                for kv in kvs:
-                    kv.kv_len.fill_(ctx_len)
-                torch.cuda.synchronize()
+                stage(1)
                 t0 = time.perf_counter()
-                for i in range(steps):
-                    x_buf.copy_(xs[i])
-                    pos_buf.fill_(ctx_len + i)
+                for i in range(n):
                     graph.launch()
                 torch.cuda.synchronize()
                 best = time.perf_counter() - t0
             return best
 
-        run(False)
-        dt = run(False)
-        dt_graph = run_graph()
-        run(True)
+        run(min(steps, 8))
+        dt = run(steps)
+        dt_graph = run_graph(min(steps, graph_steps)) if graph_steps else None
+        n_prof = min(steps, 8)
+        run(n_prof, True)
         prof = qt.qtale_profile_read(ctx)
         qt.qtale_profile_enable(ctx, False)
         ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
         lin_ms = ms["qkv_gemm"] + ms["o_gemm"] + ms["gate_up_gemm"] + ms["down_gemm"]
-        kv_bytes = k_exec * (ctx_len + steps / 2.0) * 2 * 4096 * 2
-        w_bytes = shape.params_per_layer() * bits // 8 + 4 * (shape.params_per_layer() // 128)
+        kv_bytes = k_exec * (ctx_len + n_prof / 2.0) * 2 * nkv * d * 2
         res["%.1f" % r] = {"tokens_per_s": B * steps / dt, "ms_per_step": dt * 1e3 / steps,
-                           "hip_graph_ms_per_step": dt_graph * 1e3 / steps,
+                           "hip_graph_ms_per_step": dt_graph * 1e3 / min(steps, graph_steps) if dt_graph else None,
                            "executed_per_layer": k_exec,
                            "attention_ms": ms["attention"], "attention_GBps": kv_bytes / (ms["attention"] * 1e6),
-                           "linears_ms": lin_ms, "weight_stream_GBps": w_bytes / (lin_ms * 1e6)}
-    return {"workload": "configs[2]: same stack (int%d) in decode, batch %d, %d cached K/V entries per sequence and layer "
-                        "(random fp16), %d steps per ratio, fp16 stream" % (bits, B, ctx_len, steps),
+                           "attention_frac_of_hbm_peak": kv_bytes / (ms["attention"] * 1e6) / HBM_PEAK_GBS,
+                           "linears_ms": lin_ms, "weight_stream_GBps": w_bytes / (lin_ms * 1e6),
+                           "linears_frac_of_hbm_peak": w_bytes / (lin_ms * 1e6) / HBM_PEAK_GBS,
+                           "small_kernels_ms": sum(ms[k] for k in ("router", "select", "norm1", "rope_append", "norm2"))}
+    del kvs, bufs, stack
+    torch.cuda.empty_cache()
+    alias = "" if n_buf == L else (", K/V storage of %d layers aliased round-robin by the %d layers (one layer's K/V, "
+                                   "%.1f GB, is far beyond the 256 MB memory-side cache)" % (n_buf, L, 2.0 * B * nkv * cap * d * 2 / 1e9))
+    return {"workload": "%s: %d-layer stack (hidden %d, %d/%d heads, SwiGLU %d, int%d) in decode, batch %d, %d cached K/V "
+                        "entries per sequence and layer (random fp16), %d steps per ratio, fp16 stream%s; per-kernel "
+                        "times from HIP events (they include launch gaps)"
+                        % (label, L, H, shape.n_heads, nkv, shape.inter, bits, B, ctx_len, steps, alias),
             "hbm_peak_GBps": HBM_PEAK_GBS, "by_exec_ratio": res}
+
+
+def quantized_stack(qt, si, torch, shape, L, bits=None):
+    layers = []
+    for l in range(L):
+        t = si.layer_tensors(shape, l, 0, device="cuda")
+        layers.append(qt.quantize_layer(t, bits or shape.bits, shape.group, keep_canonical=False))
+        del t
+    torch.cuda.synchronize()
+    return layers
+
+
+def prefill_section(qt, si, torch, shape, layers, B, S, ratios, label, steps=3):
+    """Prefill steps of another stack (configs[3], configs[4]): tokens/s per ratio, and the gate/up GEMM and
+    attention rates from HIP events at the first ratio."""
+    dev = "cuda"
+    L = len(layers)
+    cfg = qt.cfg_from_shape(shape)
+    stack = qt.Stack(cfg, layers)
+    T = B * S
+    offs, pos = si.equal_sequences(B, S)
+    offs, pos = offs.to(dev), pos.to(dev)
+    ws = qt.alloc_workspace(cfg, T, B, dev)
+    ctx = qt.Context()
+    out = {"workload": "%s: %d-layer stack (hidden %d, %d/%d heads, SwiGLU %d, int%d group %d), prefill %d x %d, %s stream"
+                       % (label, L, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.inter, shape.bits, shape.group, B, S,
+                          shape.act_dtype), "by_exec_ratio": {}}
+    for i, r in enumerate(ratios):
+        qt.qtale_set_exec_ratio(ctx, r)
+        k_exec = int(float(torch.tensor(r, dtype=torch.float32)) * T + 0.5)
+        xs = [si.hidden_states(shape, T, 0, extra=8000 + j, device=dev) for j in range(steps + 1)]
+        qt.qtale_stack_forward(ctx, stack, xs[0], offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for x in xs[1:]:
+            qt.qtale_stack_forward(ctx, stack, x, offs, pos, workspace=ws)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        entry = {"tokens_per_s": T / dt, "ms_per_step": dt * 1e3, "executed_per_layer": k_exec}
+        if i == 0:
+            x = si.hidden_states(shape, T, 0, extra=8100, device=dev)
+            qt.qtale_profile_enable(ctx, True)
+            qt.qtale_stack_forward(ctx, stack, x, offs, pos, workspace=ws)
+            prof = qt.qtale_profile_read(ctx)
+            qt.qtale_profile_enable(ctx, False)
+            ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
+            gu = 2.0 * k_exec * 2 * shape.inter * shape.hidden
+            n_b = k_exec / B                                       # executed tokens per sequence (equal sequences, on average)
+            att = 4.0 * n_b * n_b / 2 * shape.n_heads * shape.head_dim * B
+            entry["kernel_ms_per_launch"] = ms
+            entry["gate_up_gemm_TFLOPs"] = gu / (ms["gate_up_gemm"] * 1e-3) / 1e12
+            entry["gate_up_gemm_frac_of_mfma_peak"] = entry["gate_up_gemm_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
+            entry["attention_TFLOPs_causal"] = att / (ms["attention"] * 1e-3) / 1e12
+            entry["attention_share_of_layer"] = ms["attention"] / sum(ms.values())
+        out["by_exec_ratio"]["%.1f" % r] = entry
+        del xs
+    del ws, stack
+    torch.cuda.empty_cache()
+    return out
 
 
 def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode, layers4=None):
@@ -213,7 +322,8 @@ def int3_section(qt, si, torch, shape4, L, B, S, ratio, no_decode, layers4=None)
         del mstack, mixed
     del xs, ws
     if not no_decode:
-        out["decode"] = decode_section(qt, si, torch, layers, L, bits=3, ratios=(1.0, 0.4))["by_exec_ratio"]
+        out["decode"] = decode_section(qt, si, torch, layers, L, bits=3, ratios=(1.0, 0.4), steps=16, graph_steps=0,
+                                       label="3-bit codes")["by_exec_ratio"]
     return out
 
 
@@ -230,6 +340,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-int3", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the configs[3] (8B GQA) and configs[4] (13B) sections")
+    ap.add_argument("--decode-steps", type=int, default=256, help="generated steps per ratio in the configs[2] section")
+    ap.add_argument("--no-graph", action="store_true", help="profiling aid: leave the HIP-graph replay leg out of the decode sections")
     ap.add_argument("--decode-only", type=float, default=None, metavar="RATIO",
                     help="profiling aid: run only the decode section at this execution ratio and print its JSON")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -261,7 +374,8 @@ def main():
         del t
     torch.cuda.synchronize()
     if args.decode_only is not None:
-        print(json.dumps({"decode": decode_section(qt, si, torch, layers, L, ratios=(args.decode_only,))}))
+        print(json.dumps({"decode": decode_section(qt, si, torch, layers, L, ratios=(args.decode_only,), steps=16,
+                                                   graph_steps=0 if args.no_graph else 16)}))
         return
     stack = qt.Stack(cfg, layers)
     offs, pos = si.equal_sequences(B, S)
@@ -434,10 +548,33 @@ def main():
         int3 = int3_section(qt, si, torch, shape, L, B, S, args.ratio, args.no_decode, layers)
     decode = None
     if not args.no_decode:
-        decode = decode_section(qt, si, torch, layers, L)
-        small = decode_section(qt, si, torch, layers, L, B=8, ratios=(1.0, 0.5))
+        gs = 0 if args.no_graph else 32
+        decode = decode_section(qt, si, torch, layers, L, steps=args.decode_steps, graph_steps=gs)
+        small = decode_section(qt, si, torch, layers, L, B=8, ratios=(1.0, 0.5), steps=32, graph_steps=gs,
+                               label="same stack, batch 8")
         decode["batch_8"] = {r: {k: v[k] for k in ("tokens_per_s", "ms_per_step", "hip_graph_ms_per_step", "executed_per_layer")}
                              for r, v in small["by_exec_ratio"].items()}
+    # the other workload configurations: LLaMA-3-8B-shaped GQA prefill 4 x 4096 at ratio 0.6, and the LLaMA-13B-shaped
+    # stack (prefill 16 x 512, then decode batch 128 on 4096 cached entries) over a sweep of ratios
+    others = None
+    if not args.no_other_configs:
+        del layers, stack
+        torch.cuda.empty_cache()
+        others = {}
+        l8 = quantized_stack(qt, si, torch, si.C4, 32)
+        others["configs[3]"] = prefill_section(qt, si, torch, si.C4, l8, 4, 4096, (0.6, 1.0), "configs[3]", steps=2)
+        del l8
+        torch.cuda.empty_cache()
+        l13 = quantized_stack(qt, si, torch, si.C5, 40)
+        c5 = {"prefill": prefill_section(qt, si, torch, si.C5, l13, 16, 512, (0.5, 0.3, 1.0), "configs[4] prefill", steps=2)}
+        if not args.no_decode:
+            # 40 layers x 128 sequences x 4096 entries of K and V are 430 GB, more than the 288 GB of HBM: 12 distinct
+            # per-layer buffers (129 GB) are shared round-robin by the 40 layers
+            c5["decode"] = decode_section(qt, si, torch, l13, 40, B=128, ctx_len=4096, steps=8, ratios=(1.0, 0.5, 0.3),
+                                          base=si.C5, kv_distinct=12, graph_steps=0, label="configs[4] decode")
+        others["configs[4]"] = c5
+        del l13
+        torch.cuda.empty_cache()
 
     out = {
         "metric": "tokens/s of quantized token-adaptive layer stack vs exec ratio; % HBM/MFMA peak",
@@ -457,6 +594,7 @@ def main():
         "box_ceilings": ceilings,
         "decode": decode,
         "int3": int3,
+        "other_configs": others,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, B, S, args.ratio, L)

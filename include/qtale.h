@@ -162,7 +162,7 @@ int qtale_layer_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_
  * that forbid hipMalloc): qtale_layer_forward with the workspace taken from an array inside the library instead
  * of a caller buffer.  Same arguments, same kernels and bit-identical results; the call allocates and frees
  * nothing.  The array is QTALE_STATIC_SCRATCH_BYTES large (enough for a decode step of 128 one-token sequences
- * at hidden 5120 / 40 heads / SwiGLU 13824, or about 300 prefill tokens at hidden 4096 / SwiGLU 11008) and every
+ * at hidden 5120 / 40 heads / SwiGLU 13824, or about 250 prefill tokens at hidden 4096 / SwiGLU 11008) and every
  * GPU the library runs on holds one copy until the process ends.  A call whose workspace
  * (qtale_workspace_bytes(cfg, T, B)) is larger returns QTALE_ERR_WORKSPACE_TOO_SMALL before any GPU work.
  * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or threads) race;

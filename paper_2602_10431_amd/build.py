@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqtale.so")
-SOURCES = ["quantize.hip", "router_select.hip", "rowops.hip", "gemm_w4a16.hip", "gemm_skinny.hip", "gemm_mid.hip", "attention.hip", "qtale_api.hip"]
+SOURCES = ["quantize.hip", "router_select.hip", "rowops.hip", "gemm_w4a16.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_mid.hip", "attention.hip", "qtale_api.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

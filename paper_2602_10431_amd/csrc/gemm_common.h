@@ -21,6 +21,8 @@ struct GemmDev {
     const int32_t* idx;
     int bf16;
     int bits;                      // 4, 3 or 2: width of the weight codes
+    int ksplit;                    // decode kernel: parts K is cut into across workgroups (1 = none)
+    int epi_rt;                    // decode kernel: epilogue chosen at run time (GemmEpilogue)
 };
 
 constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
@@ -163,6 +165,7 @@ struct WBits<4> {
     static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
         return (reinterpret_cast<const u32x4_t*>(frag_base) + static_cast<size_t>(kt) * 64)[lane];
     }
+    static __device__ __forceinline__ Tile load_lane(const char* lane_ptr) { return *reinterpret_cast<const u32x4_t*>(lane_ptr); }
     static __device__ __forceinline__ SZ expand(uint32_t raw) { return expand_sz(raw); }
     static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
         const uint32_t w = j == 0 ? t.x : j == 1 ? t.y : j == 2 ? t.z : t.w;
@@ -178,6 +181,7 @@ struct WBits<2> {
     static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
         return (reinterpret_cast<const u32x2_t*>(frag_base) + static_cast<size_t>(kt) * 64)[lane];
     }
+    static __device__ __forceinline__ Tile load_lane(const char* lane_ptr) { return *reinterpret_cast<const u32x2_t*>(lane_ptr); }
     static __device__ __forceinline__ SZ expand(uint32_t raw) { return expand_sz2(raw); }
     static __device__ __forceinline__ half8_t dequant(const Tile& t, int j, const SZ& s, uint32_t magic) {
         const half2_t p0 = dequant_pair2(t, 4 * j + 0, s, magic);
@@ -198,6 +202,12 @@ struct WBits<3> {
     static constexpr int kLaneBytes = 12;
     static __device__ __forceinline__ Tile load(const void* frag_base, int kt, int lane) {
         const uint32_t* p = reinterpret_cast<const uint32_t*>(frag_base) + (static_cast<size_t>(kt) * 64 + lane) * 3;
+        Tile t;
+        t.x = p[0]; t.y = p[1]; t.z = p[2];
+        return t;
+    }
+    static __device__ __forceinline__ Tile load_lane(const char* lane_ptr) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(lane_ptr);
         Tile t;
         t.x = p[0]; t.y = p[1]; t.z = p[2];
         return t;
@@ -330,6 +340,10 @@ __device__ __forceinline__ void store_tile(const GemmDev& p, const float16_t (&a
 }
 
 hipError_t launch_gemm_skinny(GemmDev& d, int epilogue, hipStream_t stream);
+// Decode kernel (at most 64 rows per chunk): gemm_decode_plan picks the fragments per workgroup and, when
+// split_max > 1, the number of K parts (the epilogue must then be EPI_PARTIAL_F32: out = fp32 [parts][M_max][ldo]).
+int gemm_decode_plan(const GemmDev& d, int epilogue, int split_max, int* nwn_out);
+hipError_t launch_gemm_decode(GemmDev& d, int epilogue, int nwn, int split, hipStream_t stream);
 hipError_t launch_gemm_mid(GemmDev& d, int epilogue, hipStream_t stream);
 
 }  // namespace qtale

@@ -342,6 +342,27 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     // workgroups).  Up to 64 rows the skinny kernel streams the weights once; up to 256 rows it runs one 64-row
     // chunk per workgroup (measured on 13B-shaped linears at 128 rows: 26-59 us against 64-178 us here; at 256
     // rows the two are level).
+    if (a.n_parts) *a.n_parts = 0;
+    if (d.M_max <= kGemmPartRows) {
+        // decode steps: one-fragment waves that share activation tiles; hidden-size-wide outputs (o-proj, down-proj)
+        // also cut K across workgroups when the caller can add the partial tiles
+        const bool resid = a.epilogue == EPI_RESID_F32 || a.epilogue == EPI_RESID_SCATTER;
+        // (measured, 7B shape at 64 rows: the 12288-column q|k|v output, whose 192 two-fragment blocks nearly fill the
+        // chip without cutting K, takes 17.6 us on the K-sliced skinny kernel and 20.3 us on the decode kernel)
+        const bool wide_store = a.epilogue == EPI_STORE_F16 && d.M_max > 32 && d.vf_total >= 256;
+        if (!resid && !wide_store) {
+            int nwn;
+            gemm_decode_plan(d, a.epilogue, 1, &nwn);
+            return launch_gemm_decode(d, a.epilogue, nwn, 1, stream);
+        }
+        if (a.part && a.n_parts) {
+            int nwn;
+            const int split = gemm_decode_plan(d, EPI_PARTIAL_F32, kGemmPartMax, &nwn);
+            d.out = a.part;
+            *a.n_parts = split;
+            return launch_gemm_decode(d, EPI_PARTIAL_F32, nwn, split, stream);
+        }
+    }
     if (d.M_max <= 256) return launch_gemm_skinny(d, a.epilogue, stream);
     // A few hundred rows: so few 128 x 256 tiles that a CU holds at most one workgroup, whose k-loop then runs
     // at one memory latency per k-tile.  The 64-row kernel with its deep prefetch rings takes over while its own

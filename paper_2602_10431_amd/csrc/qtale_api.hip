@@ -47,6 +47,7 @@ struct Workspace {
     float* h;              // [T][H] fp32
     void* act;             // [T][I] fp16
     float* attn_part;      // [min(T, kAttnSplitRows)][nh][kAttnSplitMax][d + 2] fp32: key-range partials of decode attention
+    float* gemm_part;      // [kGemmPartMax][min(T, kGemmPartRows)][H] fp32: K-part partial tiles of the decode o-/down-proj
     size_t total;
 };
 
@@ -74,6 +75,8 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
     w.act = take(Tz * c->inter * 2);
     w.attn_part = reinterpret_cast<float*>(take(static_cast<size_t>(T < kAttnSplitRows ? T : kAttnSplitRows) * c->n_heads *
                                                 kAttnSplitMax * (c->head_dim + 2) * 4));
+    w.gemm_part = reinterpret_cast<float*>(take(static_cast<size_t>(kGemmPartMax) * (T < kGemmPartRows ? T : kGemmPartRows) *
+                                                c->hidden * 4));
     w.total = off;
     return w;
 }
@@ -217,6 +220,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         HIP_TRY(launch_gather_rmsnorm(x, bf16, H, ws.idx, count, M_max, w->norm1, c->rms_eps, ws.nbuf, stream));
     }
     const int qkv_w = (nh + 2 * nkv) * d;
+    int o_parts = 0;
     {
         Prof pr(ctx, stream, 3);
         GemmArgs g{};
@@ -251,11 +255,16 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         g.A = ws.attn; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = nh * d; g.group = c->group; g.bits = lbits; g.n_w = 1;
         g.w[0] = {w->o.prepacked, w->o.N, w->o.K};
         g.epilogue = EPI_RESID_F32; g.out = ws.h; g.ldo = H; g.resid = x; g.idx = ws.idx; g.bf16 = bf16;
+        g.part = M_max <= kGemmPartRows ? ws.gemm_part : nullptr; g.n_parts = &o_parts;
         HIP_TRY(launch_gemm_w4a16(g, stream));
     }
     {
         Prof pr(ctx, stream, 7);
-        HIP_TRY(launch_rmsnorm_f32(ws.h, H, count, M_max, w->norm2, bf16, c->rms_eps, ws.nbuf, stream));
+        if (o_parts > 0)       // the o-proj left K-part partial tiles: add them and the residual here
+            HIP_TRY(launch_reduce_rmsnorm(ws.gemm_part, o_parts, x, bf16, ws.idx, H, count, M_max, w->norm2, c->rms_eps,
+                                          ws.h, ws.nbuf, stream));
+        else
+            HIP_TRY(launch_rmsnorm_f32(ws.h, H, count, M_max, w->norm2, bf16, c->rms_eps, ws.nbuf, stream));
     }
     {
         Prof pr(ctx, stream, 8);
@@ -272,7 +281,11 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         g.A = ws.act; g.count = count; g.M_max = M_max; g.rows_exact = ratio_mode; g.K = I; g.group = c->group; g.bits = lbits; g.n_w = 1;
         g.w[0] = {w->down.prepacked, w->down.N, w->down.K};
         g.epilogue = EPI_RESID_SCATTER; g.out = x; g.ldo = H; g.resid = ws.h; g.idx = ws.idx; g.bf16 = bf16;
+        int d_parts = 0;
+        g.part = M_max <= kGemmPartRows ? ws.gemm_part : nullptr; g.n_parts = &d_parts;
         HIP_TRY(launch_gemm_w4a16(g, stream));
+        if (d_parts > 0)
+            HIP_TRY(launch_reduce_scatter(ws.gemm_part, d_parts, ws.h, H, ws.idx, count, M_max, x, bf16, stream));
     }
     return QTALE_OK;
 }

@@ -72,8 +72,18 @@ struct RopeArgs {
 };
 hipError_t launch_rope_append(const RopeArgs& a, hipStream_t stream);
 
+// Consumers of the decode GEMM's partial tiles (part = fp32 [n_parts][max_rows][H], added in part order):
+//   h[i] = x[idx[i]] + sum(part[.][i]);  n2[i] = fp16(rmsnorm(h[i]) * gain)          (after the o-proj)
+hipError_t launch_reduce_rmsnorm(const float* part, int n_parts, const void* x, int bf16, const int32_t* idx, int H,
+                                 const int32_t* count, int max_rows, const void* gain, float eps, float* h,
+                                 void* out_f16, hipStream_t stream);
+//   x[idx[i]] = act(h[i] + sum(part[.][i]))                                           (after the down-proj)
+hipError_t launch_reduce_scatter(const float* part, int n_parts, const float* h, int H, const int32_t* idx,
+                                 const int32_t* count, int max_rows, void* x, int bf16, hipStream_t stream);
+
 // ---- W4A16 / W3A16 GEMM ---------------------------------------------------------------------------------
-enum GemmEpilogue { EPI_STORE_F16 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU_F16 = 2, EPI_RESID_SCATTER = 3 };
+enum GemmEpilogue { EPI_STORE_F16 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU_F16 = 2, EPI_RESID_SCATTER = 3,
+                    EPI_PARTIAL_F32 = 4 };   // fp32 partial tiles [parts][M_max][ldo], decode kernel only
 
 struct GemmWeights {
     const void* prepacked;
@@ -96,7 +106,14 @@ struct GemmArgs {
     const void* resid;         // RESID_F32: x (act dtype, rows via idx); RESID_SCATTER: h fp32 [M][ldo]
     const int32_t* idx;        // compact row -> token row (RESID_F32 reads, RESID_SCATTER writes)
     int bf16;                  // act dtype of x
+    // Decode steps (M_max <= kGemmPartRows) with a RESID_* epilogue: when `part` is given the GEMM may cut K across
+    // workgroups and write fp32 partial tiles [*n_parts][M_max][ldo] there INSTEAD of applying its epilogue; the
+    // caller then runs the consumer that adds the parts (launch_reduce_rmsnorm / launch_reduce_scatter).
+    float* part;               // nullable: room for kGemmPartMax x M_max x ldo floats
+    int* n_parts;              // host out, required with `part`: 0 = epilogue applied as usual, else parts written
 };
+constexpr int kGemmPartRows = 64;
+constexpr int kGemmPartMax = 4;
 hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream);
 
 // ---- attention over executed tokens ---------------------------------------------------------------

@@ -150,6 +150,144 @@ hipError_t launch_rmsnorm_f32(const float* h, int H, const int32_t* count, int m
     return hipGetLastError();
 }
 
+// Consumers of the decode GEMM's fp32 partial tiles (part[s][i][c], s = K part): the parts of a row are added
+// in part order, so the result does not depend on scheduling.
+//   h[i] = x[idx[i]] + sum_s part[s][i]   (post-attention residual, fp32)   and   out[i] = fp16(rmsnorm(h[i]) * gain)
+// One workgroup per executed row; the row stays in registers between the reduction and the scaling (up to 8192
+// columns; wider rows are recomputed from the stored h).
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+reduce_rmsnorm_kernel(const float* __restrict__ part, int n_parts, size_t part_stride, const uint16_t* __restrict__ x,
+                      const int32_t* __restrict__ idx, int H, const int32_t* __restrict__ count,
+                      const uint16_t* __restrict__ gain, float eps, float* __restrict__ h, uint16_t* __restrict__ out) {
+    __shared__ float red[4];
+    const int i = blockIdx.x;
+    if (i >= *count) return;
+    const U2* xr = reinterpret_cast<const U2*>(x + static_cast<size_t>(idx[i]) * H);
+    const float4_t* pr = reinterpret_cast<const float4_t*>(part + static_cast<size_t>(i) * H);
+    const size_t pstep = part_stride / 4;
+    float4_t* hr = reinterpret_cast<float4_t*>(h + static_cast<size_t>(i) * H);
+    const U2* gr = reinterpret_cast<const U2*>(gain);
+    U2* orow = reinterpret_cast<U2*>(out + static_cast<size_t>(i) * H);
+    const int chunks = H >> 2;
+    constexpr int KEEP = 8;
+    float4_t keep[KEEP];
+    float ss = 0.0f;
+    auto row_value = [&](int c) {
+        const U2 xv = xr[c];
+        float4_t v;
+        v[0] = act_to_float<BF16>(static_cast<uint16_t>(xv.x & 0xffffu));
+        v[1] = act_to_float<BF16>(static_cast<uint16_t>(xv.x >> 16));
+        v[2] = act_to_float<BF16>(static_cast<uint16_t>(xv.y & 0xffffu));
+        v[3] = act_to_float<BF16>(static_cast<uint16_t>(xv.y >> 16));
+        // all parts are requested before any is added (independent loads); parts past n_parts repeat part 0, unused
+        float4_t pv[kGemmPartMax];
+#pragma unroll
+        for (int s = 0; s < kGemmPartMax; ++s) pv[s] = pr[(s < n_parts ? s : 0) * pstep + c];
+        float4_t acc = pv[0];
+#pragma unroll
+        for (int s = 1; s < kGemmPartMax; ++s)
+            if (s < n_parts) acc += pv[s];
+        return v + acc;
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        keep[u] = float4_t{0.f, 0.f, 0.f, 0.f};
+        if (c < chunks) {
+            keep[u] = row_value(c);
+            hr[c] = keep[u];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss = fmaf(keep[u][e], keep[u][e], ss);
+    }
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) {
+        const float4_t v = row_value(c);
+        hr[c] = v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss = fmaf(v[e], v[e], ss);
+    }
+    ss = block_sum_256(ss, red);
+    const float inv = 1.0f / sqrtf(ss / static_cast<float>(H) + eps);
+    auto emit = [&](int c, const float4_t& v) {
+        const U2 g = gr[c];
+        const float g0 = act_to_float<BF16>(static_cast<uint16_t>(g.x & 0xffffu));
+        const float g1 = act_to_float<BF16>(static_cast<uint16_t>(g.x >> 16));
+        const float g2 = act_to_float<BF16>(static_cast<uint16_t>(g.y & 0xffffu));
+        const float g3 = act_to_float<BF16>(static_cast<uint16_t>(g.y >> 16));
+        U2 o;
+        o.x = static_cast<uint32_t>(float_to_half_bits(v[0] * inv * g0)) | (static_cast<uint32_t>(float_to_half_bits(v[1] * inv * g1)) << 16);
+        o.y = static_cast<uint32_t>(float_to_half_bits(v[2] * inv * g2)) | (static_cast<uint32_t>(float_to_half_bits(v[3] * inv * g3)) << 16);
+        orow[c] = o;
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = threadIdx.x + u * 256;
+        if (c < chunks) emit(c, keep[u]);
+    }
+    for (int c = threadIdx.x + KEEP * 256; c < chunks; c += 256) emit(c, row_value(c));
+}
+
+hipError_t launch_reduce_rmsnorm(const float* part, int n_parts, const void* x, int bf16, const int32_t* idx, int H,
+                                 const int32_t* count, int max_rows, const void* gain, float eps, float* h,
+                                 void* out_f16, hipStream_t stream) {
+    if (max_rows == 0) return hipSuccess;
+    const dim3 grid(max_rows), block(256);
+    const size_t stride = static_cast<size_t>(max_rows) * H;
+    if (bf16)
+        hipLaunchKernelGGL(reduce_rmsnorm_kernel<true>, grid, block, 0, stream, part, n_parts, stride,
+                           reinterpret_cast<const uint16_t*>(x), idx, H, count, reinterpret_cast<const uint16_t*>(gain), eps, h,
+                           reinterpret_cast<uint16_t*>(out_f16));
+    else
+        hipLaunchKernelGGL(reduce_rmsnorm_kernel<false>, grid, block, 0, stream, part, n_parts, stride,
+                           reinterpret_cast<const uint16_t*>(x), idx, H, count, reinterpret_cast<const uint16_t*>(gain), eps, h,
+                           reinterpret_cast<uint16_t*>(out_f16));
+    return hipGetLastError();
+}
+
+//   x[idx[i]] = act dtype( h[i] + sum_s part[s][i] ): the layer's output rows written back into the residual stream
+// (Eq. 1 for executed tokens; bypassed rows are not touched, Eq. 3).  A row is cut over gridDim.y workgroups.
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+reduce_scatter_kernel(const float* __restrict__ part, int n_parts, size_t part_stride, const float* __restrict__ h, int H,
+                      const int32_t* __restrict__ idx, const int32_t* __restrict__ count, uint16_t* __restrict__ x) {
+    const int i = blockIdx.x;
+    if (i >= *count) return;
+    const float4_t* pr = reinterpret_cast<const float4_t*>(part + static_cast<size_t>(i) * H);
+    const size_t pstep = part_stride / 4;
+    const float4_t* hr = reinterpret_cast<const float4_t*>(h + static_cast<size_t>(i) * H);
+    U2* orow = reinterpret_cast<U2*>(x + static_cast<size_t>(idx[i]) * H);
+    const int chunks = H >> 2;
+    for (int c = blockIdx.y * 256 + threadIdx.x; c < chunks; c += 256 * gridDim.y) {
+        float4_t pv[kGemmPartMax];
+#pragma unroll
+        for (int s = 0; s < kGemmPartMax; ++s) pv[s] = pr[(s < n_parts ? s : 0) * pstep + c];
+        float4_t acc = pv[0];
+#pragma unroll
+        for (int s = 1; s < kGemmPartMax; ++s)
+            if (s < n_parts) acc += pv[s];
+        const float4_t v = hr[c] + acc;
+        U2 o;
+        o.x = static_cast<uint32_t>(float_to_act<BF16>(v[0])) | (static_cast<uint32_t>(float_to_act<BF16>(v[1])) << 16);
+        o.y = static_cast<uint32_t>(float_to_act<BF16>(v[2])) | (static_cast<uint32_t>(float_to_act<BF16>(v[3])) << 16);
+        orow[c] = o;
+    }
+}
+
+hipError_t launch_reduce_scatter(const float* part, int n_parts, const float* h, int H, const int32_t* idx,
+                                 const int32_t* count, int max_rows, void* x, int bf16, hipStream_t stream) {
+    if (max_rows == 0) return hipSuccess;
+    const dim3 grid(max_rows, (H / 4 + 255) / 256), block(256);     // one 16-byte chunk per thread
+    const size_t stride = static_cast<size_t>(max_rows) * H;
+    if (bf16)
+        hipLaunchKernelGGL(reduce_scatter_kernel<true>, grid, block, 0, stream, part, n_parts, stride, h, H, idx, count,
+                           reinterpret_cast<uint16_t*>(x));
+    else
+        hipLaunchKernelGGL(reduce_scatter_kernel<false>, grid, block, 0, stream, part, n_parts, stride, h, H, idx, count,
+                           reinterpret_cast<uint16_t*>(x));
+    return hipGetLastError();
+}
+
 // Rotary embedding, half-split pairing (element i with i + d/2), angle = position * base^(-2i/d), at
 // the ORIGINAL absolute position of the token (a bypassed token leaves a gap in the positions seen by
 // a layer).  One workgroup per executed row: the d/2 (cos, sin) pairs of the row's position are

@@ -230,6 +230,16 @@ def test_decode_step_gqa_head128(qt):
     _cache_case(qt, shape, [1] * 5, [300, 2, 77, 129, 64], [290, 2, 70, 129, 60], 320, 5, 0.8)
 
 
+@pytest.mark.parametrize("bits,B,ratio", [(4, 60, 1.0), (3, 64, 0.45), (2, 33, 1.0), (4, 7, 1.0)])
+def test_decode_step_with_k_cut_across_workgroups(qt, bits, B, ratio):
+    # hidden 1024 (32 weight fragments): the o-proj (K = 1024, 16 k-tiles) and the down-proj (K = 2744: 43 k-tiles,
+    # the last one ragged) are cut into 4 K parts whose fp32 partial tiles the following kernels add; 60 / 33 rows
+    # run two 32-row fragments, 29 / 7 rows one; gate/up fragments mix 16 gate and 16 up rows
+    shape = si.LayerShape(1024, 8, 4, 128, 2744, bits, 128, "bf16")
+    lens = [int(v) for v in np.random.default_rng(B).integers(1, 200, size=B)]
+    _cache_case(qt, shape, [1] * B, lens, lens, 208, 70 + bits, ratio)
+
+
 def test_chunked_prefill_with_cache(qt):
     shape = si.LayerShape(256, 4, 2, 64, 512, 4, 32, "fp16")
     _cache_case(qt, shape, [40, 150, 7], [10, 0, 90], [8, 0, 75], 256, 6, 0.7)
