@@ -461,10 +461,23 @@ def main():
         run(xs[1:])
         torch.cuda.synchronize()
         dt_thr = (time.perf_counter() - t0) / 3
+        fresh_ratio = float(cnt.sum().item()) / (L * T)
+        # like for like: ratio mode at the executed fraction the threshold produced on these batches (the per-layer
+        # counts of threshold mode are not multiples of the 128-row tile, ratio 0.5 of 8192 is)
+        qt.qtale_set_exec_ratio(ctx, fresh_ratio)
+        xs = batches(4, 5000)
+        run(xs[:1])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(xs[1:])
+        torch.cuda.synchronize()
+        dt_same = (time.perf_counter() - t0) / 3
         threshold = {"target_ratio": args.ratio, "theta": theta, "calibration_ratio": r_avg,
                      "candidates_evaluated": len(seen), "calibration_s": t_cal,
-                     "fresh_batch_ratio": float(cnt.sum().item()) / (L * T),
-                     "tokens_per_s": T / dt_thr, "ms_per_step": dt_thr * 1e3}
+                     "fresh_batch_ratio": fresh_ratio,
+                     "tokens_per_s": T / dt_thr, "ms_per_step": dt_thr * 1e3,
+                     "ratio_mode_at_the_same_executed_fraction_ms_per_step": dt_same * 1e3,
+                     "overhead_vs_ratio_mode": dt_thr / dt_same - 1.0}
         qt.qtale_set_exec_ratio(ctx, args.ratio)
     # the same stack with the paper's two-output MLP router (one hidden ReLU layer of 16 units) instead of the
     # linear one

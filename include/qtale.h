@@ -129,8 +129,10 @@ typedef struct {
  * value at that layer).  k_cache/v_cache: [B][n_kv_heads][cap][head_dim] fp16 (the entries of one sequence
  * and head are contiguous: decode attention streams them at the full memory rate); kv_len [B] int32 device:
  * entries already present per sequence.  A forward call appends the executed tokens of sequence b (keys
- * after rotary embedding) at kv_len[b].. and adds their number to kv_len[b].  The caller guarantees
- * kv_len[b] + (tokens of sequence b in the call) <= cap; rows that would not fit are dropped. */
+ * after rotary embedding) at kv_len[b].. and adds their number to kv_len[b].  The caller should guarantee
+ * kv_len[b] + (tokens of sequence b in the call) <= cap.  If it does not, the entries that would not fit are
+ * dropped (the newest tokens of the call), kv_len[b] stops at cap, and those tokens' own queries attend to the cap
+ * entries present: kv_len[b] == cap after a call is the caller's sign that the cache is full. */
 typedef struct {
     void* k_cache;
     void* v_cache;

@@ -102,14 +102,13 @@ flash_prefill_kernel(AttnDev p) {
     const int wave_hi = base_len + q_lo + min(wave * 32 + 31, q_cnt - 1) + 1;   // largest limit in the wave
     const int wave_lo = base_len + q_lo + min(wave * 32, q_cnt - 1) + 1;        // smallest limit in the wave
     const half_t* qrow = p.qkv + static_cast<size_t>(row_begin + q_local) * p.width + h * D;
+    // The queries stay as stored; the factor log2(e)/sqrt(d) is applied in fp32 inside the exponent's fused
+    // multiply-add (folding it into the fp16 queries would round it, and every product, to 11 bits: an error in
+    // the logits that grows with their magnitude).
     half8_t qf[KS];
-    const half_t qs = static_cast<half_t>(p.scale_log2);         // fold log2(e)/sqrt(d) into the queries
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        qf[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * lhi);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[s][e] *= qs;
-    }
+    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * lhi);
+    const float sc = p.scale_log2;
 
     float16_t o[DF];
 #pragma unroll
@@ -213,14 +212,14 @@ flash_prefill_kernel(AttnDev p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kf][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);
+            const float m_new = fmaxf(m_run, mx * sc);           // running maximum in units of log2 (sc > 0: same arg-max)
             float psum = 0.0f;
             half8_t pf[4];
 #pragma unroll
             for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(st[kf][r] - m_new);
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(st[kf][r], sc, -m_new));
                     psum += pv;
                     pf[kf * 2 + (r >> 3)][r & 7] = static_cast<half_t>(pv);
                 }

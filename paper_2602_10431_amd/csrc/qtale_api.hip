@@ -210,7 +210,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         s.z_thr = ratio_mode ? 0.0f : theta_to_logit(ctx->value);
         s.seq_offsets = seq_offsets; s.B = B;
         s.idx = ws.idx; s.count = count; s.cu_exec = ws.cu_exec; s.row_seq = ws.row_seq;
-        s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old;
+        s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old; s.kv_cap = kv ? kv->cap : 0;
         s.idx_copy = sel_idx; s.count_copy = sel_count;
         HIP_TRY(launch_select(s, stream));
     }

@@ -39,6 +39,7 @@ struct SelectArgs {
     int32_t* row_seq;          // [T] out: sequence of each executed row (nullable)
     int32_t* kv_len;           // [B] in/out (nullable): advanced by the executed count of each sequence
     int32_t* kv_old;           // [B] out (nullable unless kv_len given): kv_len before the call
+    int kv_cap;                // capacity of the cache behind kv_len (0 = unknown): kv_len is not advanced beyond it
     int32_t* idx_copy;         // nullable: second destination for idx (caller-visible output)
     int32_t* count_copy;       // nullable
 };

@@ -255,10 +255,13 @@ hipError_t launch_router_mlp(const void* x, int bf16, int T, int H, const float*
     return hipGetLastError();
 }
 
-// fp32 -> uint32 key whose unsigned order is the float order (-0 is first folded onto +0).
+// fp32 -> uint32 key whose unsigned order is the float order (-0 is first folded onto +0).  A NaN score gets the
+// smallest key: it ranks below every number, also below -inf, so it never meets a threshold (as in
+// threshold_bins_kernel) and is taken by the ratio rule only after every other token.
 __device__ __forceinline__ uint32_t order_key(float f) {
     f += 0.0f;
     const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
@@ -455,7 +458,8 @@ select_compact_kernel(SelectArgs a) {
             const int cn = offs_cached ? scu[b + 1] : a.cu_exec[b + 1];
             const int old = a.kv_len[b];
             a.kv_old[b] = old;
-            a.kv_len[b] = old + (cn - cb);
+            // entries that do not fit are dropped by the append; the length never passes the capacity
+            a.kv_len[b] = a.kv_cap > 0 ? min(old + (cn - cb), max(old, a.kv_cap)) : old + (cn - cb);
         }
     }
 }

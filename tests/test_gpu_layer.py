@@ -9,10 +9,9 @@ import torch
 
 import synth_inputs as si
 from oracle import qtale_oracle as orc
-from tests.helpers import cfg_dict, oracle_layer, to_f64
+from tests.helpers import cfg_dict, check_parity, oracle_layer, to_f64
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
 
 
 @pytest.fixture(scope="module")
@@ -48,7 +47,7 @@ def _check_layer(qt, shape, T, lens, mode, val, seed, std=0.02, starts=None):
     skipped = np.setdiff1d(np.arange(T), widx)
     assert torch.equal(got[skipped], x[skipped])                 # bypassed rows: bit-identical
     err = orc.parity_error(to_f64(got)[widx], want[widx])
-    assert err <= TOL, err
+    check_parity(err, shape.act_dtype, ("layer", shape.hidden, shape.bits, T, mode, val), hidden=shape.hidden)
     return err
 
 
@@ -69,6 +68,19 @@ def test_config1_shape_with_unit_scale_layer_function(qt, mode, val):
 def test_layer_ragged_sequences_gqa_bf16_head128(qt):
     shape = si.LayerShape(512, 4, 2, 128, 1376, 4, 128, "bf16")
     _check_layer(qt, shape, 333, [100, 1, 200, 32], "ratio", 0.6, seed=1, std=0.057, starts=[0, 5, 17, 1000])
+
+
+@pytest.mark.parametrize("std,d", [(0.14, 64), (0.10, 128)])
+def test_layer_with_large_attention_logits(qt, std, d):
+    # weights up to 1.75 times the unit scale: attention logits reach +-25, where a softmax scale rounded to 11 bits
+    # (folded into fp16 queries) costs visibly: with the scale applied in fp32 the (0.14, 64) case measures 1.49e-2,
+    # with the folded scale 1.75e-2.  700 executed tokens in one sequence run the matrix-core attention kernel over
+    # several key tiles.  (What remains is the fp16 rounding of the GEMM operands itself: a CPU emulation of the layer
+    # with fp16 roundings at the kernels' rounding points gives 1.53e-2 for this case, and at still larger weights,
+    # std 0.2 with head_dim 128, 4.4e-2 on the GPU and in the emulation alike - beyond the contract for any
+    # fp16-operand pipeline, which is why the sweep stops here.)
+    shape = si.LayerShape(256, 256 // d, 256 // d, d, 688, 4, 32, "fp16")
+    _check_layer(qt, shape, 700, [700], "ratio", 1.0, seed=31, std=std)
 
 
 def test_layer_spans_several_row_tiles(qt):
@@ -132,7 +144,7 @@ def test_layer_with_two_output_mlp_router(qt, mode, val):
     assert 0 < len(widx) < T and np.array_equal(idx, widx)
     skipped = np.setdiff1d(np.arange(T), widx)
     assert torch.equal(got[skipped], x[skipped])
-    assert orc.parity_error(to_f64(got)[widx], want[widx]) <= TOL
+    check_parity(orc.parity_error(to_f64(got)[widx], want[widx]), shape.act_dtype, "layer with MLP router", hidden=shape.hidden)
 
 
 def test_threshold_mode_with_more_tiles_than_resident_workgroups(qt):
@@ -155,15 +167,15 @@ def _cache_case(qt, shape, lens, starts, old_lens, cap, seed, ratio):
     okv = orc.KVCache(to_f64(kc), to_f64(vc), old_lens)
     want, widx, _ = orc.layer_forward(to_f64(x), p, cfg_dict(shape), offs.numpy(), pos.numpy(), "ratio", ratio, okv)
     assert np.array_equal(idx, widx)
-    assert orc.parity_error(to_f64(got)[widx], want[widx]) <= TOL
+    check_parity(orc.parity_error(to_f64(got)[widx], want[widx]), shape.act_dtype, ("cache case", shape.hidden, shape.bits, T), hidden=shape.hidden)
     assert np.array_equal(kv.kv_len.cpu().numpy(), okv.kv_len)
     gk, gv = to_f64(kv.k_token_major().cpu()), to_f64(kv.v_token_major().cpu())
     for b in range(B):
         n0, n1 = old_lens[b], int(okv.kv_len[b])
         assert np.array_equal(gk[b, :n0], okv.k[b, :n0])         # old entries untouched
         if n1 > n0:
-            assert orc.parity_error(gk[b, n0:n1], okv.k[b, n0:n1]) <= TOL
-            assert orc.parity_error(gv[b, n0:n1], okv.v[b, n0:n1]) <= TOL
+            check_parity(orc.parity_error(gk[b, n0:n1], okv.k[b, n0:n1]), "fp16", "appended keys")
+            check_parity(orc.parity_error(gv[b, n0:n1], okv.v[b, n0:n1]), "fp16", "appended values")
         assert np.array_equal(gk[b, n1:], to_f64(kc)[b, n1:])    # nothing written past the new length
 
 
@@ -272,7 +284,7 @@ def test_stack_teacher_forced(qt):
             assert k == len(widx) and np.array_equal(idx[l, :k].cpu().numpy(), widx)
             skipped = np.setdiff1d(np.arange(T), widx)
             assert torch.equal(xout[skipped], xin[skipped])
-            assert orc.parity_error(to_f64(xout)[widx], want[widx]) <= TOL
+            check_parity(orc.parity_error(to_f64(xout)[widx], want[widx]), shape.act_dtype, ("stack layer", l, mode), hidden=shape.hidden)
 
 
 def test_mixed_two_and_four_bit_stack_teacher_forced(qt):
@@ -301,7 +313,7 @@ def test_mixed_two_and_four_bit_stack_teacher_forced(qt):
         want, widx, _ = orc.layer_forward(to_f64(xin), p, cfg_dict(base), offs.numpy(), pos.numpy(), "ratio", 0.6)
         k = int(cnt[l].item())
         assert k == len(widx) and np.array_equal(idx[l, :k].cpu().numpy(), widx)
-        assert orc.parity_error(to_f64(xout)[widx], want[widx]) <= TOL
+        check_parity(orc.parity_error(to_f64(xout)[widx], want[widx]), base.act_dtype, ("mixed stack layer", l), hidden=base.hidden)
 
 
 def test_two_bit_layer_group128_bf16(qt):
