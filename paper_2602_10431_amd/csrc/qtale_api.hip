@@ -195,6 +195,13 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     float* z = scores ? scores : ws.z;
     int32_t* count = ws.scalars;
 
+    SelectArgs s{};
+    s.z = z; s.T = T; s.mode = ratio_mode ? 0 : 1; s.k = k;
+    s.z_thr = ratio_mode ? 0.0f : theta_to_logit(ctx->value);
+    s.seq_offsets = seq_offsets; s.B = B;
+    s.idx = ws.idx; s.count = count; s.cu_exec = ws.cu_exec; s.row_seq = ws.row_seq;
+    s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old; s.kv_cap = kv ? kv->cap : 0;
+    s.idx_copy = sel_idx; s.count_copy = sel_count;
     {
         Prof pr(ctx, stream, 0);
         if (w->router_hidden > 0)
@@ -203,21 +210,20 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         else
             HIP_TRY(launch_router_score(x, bf16, T, H, w->router_w, w->router_b, z, stream));
     }
-    {
+    if (fused_select_norm_fits(T, M_max)) {
+        // decode-sized call: decision, compaction and gather + RMSNorm 1 in one launch
         Prof pr(ctx, stream, 1);
-        SelectArgs s{};
-        s.z = z; s.T = T; s.mode = ratio_mode ? 0 : 1; s.k = k;
-        s.z_thr = ratio_mode ? 0.0f : theta_to_logit(ctx->value);
-        s.seq_offsets = seq_offsets; s.B = B;
-        s.idx = ws.idx; s.count = count; s.cu_exec = ws.cu_exec; s.row_seq = ws.row_seq;
-        s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old; s.kv_cap = kv ? kv->cap : 0;
-        s.idx_copy = sel_idx; s.count_copy = sel_count;
-        HIP_TRY(launch_select(s, stream));
-    }
-    if (M_max == 0) return QTALE_OK;
-    {
-        Prof pr(ctx, stream, 2);
-        HIP_TRY(launch_gather_rmsnorm(x, bf16, H, ws.idx, count, M_max, w->norm1, c->rms_eps, ws.nbuf, stream));
+        HIP_TRY(launch_select_norm(x, bf16, H, z, w->norm1, c->rms_eps, ws.nbuf, s, M_max, stream));
+    } else {
+        {
+            Prof pr(ctx, stream, 1);
+            HIP_TRY(launch_select(s, stream));
+        }
+        if (M_max == 0) return QTALE_OK;
+        {
+            Prof pr(ctx, stream, 2);
+            HIP_TRY(launch_gather_rmsnorm(x, bf16, H, ws.idx, count, M_max, w->norm1, c->rms_eps, ws.nbuf, stream));
+        }
     }
     const int qkv_w = (nh + 2 * nkv) * d;
     int o_parts = 0;

@@ -45,6 +45,13 @@ struct SelectArgs {
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 
+// Decode-sized calls: selection / compaction and gather + RMSNorm 1 in one launch, reading the scores z [T] a router
+// kernel has written; same outputs as launch_select + launch_gather_rmsnorm.  Only valid when
+// fused_select_norm_fits(T, max_rows); max_rows > 0 is the host bound on executed rows.
+bool fused_select_norm_fits(int T, int max_rows);
+hipError_t launch_select_norm(const void* x, int bf16, int H, const float* z, const void* gain, float eps, void* out_f16,
+                              const SelectArgs& s, int max_rows, hipStream_t stream);
+
 // Threshold calibration: bins[b] (kThetaGrid + 1 counters, cleared here) = number of scores that reach exactly
 // b of the kThetaGrid ascending thresholds zthr_dev (device array).
 constexpr int kThetaGrid = 50;

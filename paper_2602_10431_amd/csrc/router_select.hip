@@ -473,6 +473,163 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---- decode-sized calls: decision, compaction and the first normalisation in ONE launch -------------------------
+// With a few dozen tokens (a decode step: one token per sequence) selection and gather + RMSNorm as two launches are
+// pure launch and latency cost.  Here workgroup i produces compact row i on its own:
+//   1. every workgroup reads the T scores the router kernel wrote (Eq. 2) and turns them into order keys in LDS;
+//   2. every workgroup takes the decision (Eq. 9 / the k largest, ties to the lower index) on those keys: rank by
+//      counting, exclusive prefix of the executed flags by counting;
+//   3. workgroup i normalises the row of the i-th executed token (App. B.2 gather + RMSNorm); workgroup 0 also writes the
+//      call-wide results (ascending indices, count, per-sequence offsets, row -> sequence map, cache lengths).
+// The redundant decision costs T LDS reads per thread, which bounds T (kFusedMaxT).
+constexpr int kFusedMaxT = 256;
+
+struct FusedArgs {
+    const uint16_t* x; int H; const float* z; const uint16_t* gain; float eps; uint16_t* out;
+    SelectArgs s;
+};
+
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+select_norm_kernel(FusedArgs a) {
+    __shared__ __align__(16) uint32_t skey[kFusedMaxT];
+    __shared__ uint32_t spre[kFusedMaxT + 1];
+    __shared__ unsigned long long smask[4];
+    __shared__ int srow;
+    __shared__ float red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T = a.s.T, H = a.H;
+    const int chunks = H >> 3;
+    // 1. order keys of the scores the router kernel left in z (0 = below every real key for the padding)
+    skey[tid] = tid < T ? order_key(a.z[tid]) : 0u;
+    __syncthreads();
+    // 2. decision: threshold mode compares with the threshold's key, ratio mode ranks
+    const uint32_t key = skey[tid];
+    bool exec = false;
+    if (a.s.mode == 0) {
+        uint32_t rank = 0u;
+        const int T4 = (T + 3) >> 2;
+        const uint4* k4 = reinterpret_cast<const uint4*>(skey);
+#pragma unroll 4
+        for (int q = 0; q < T4; ++q) {                              // same address in every lane: LDS broadcast reads
+            const uint4 kk = k4[q];
+            const int u = q << 2;
+            rank += (kk.x > key || (kk.x == key && u < tid)) ? 1u : 0u;
+            rank += (kk.y > key || (kk.y == key && u + 1 < tid)) ? 1u : 0u;
+            rank += (kk.z > key || (kk.z == key && u + 2 < tid)) ? 1u : 0u;
+            rank += (kk.w > key || (kk.w == key && u + 3 < tid)) ? 1u : 0u;
+        }
+        exec = tid < T && static_cast<int>(rank) < a.s.k;
+    } else {
+        exec = tid < T && key >= order_key(a.s.z_thr);
+    }
+    const unsigned long long mask = __ballot(exec);
+    if (lane == 0) smask[wave] = mask;
+    __syncthreads();
+    int before = __popcll(mask & ((1ull << lane) - 1ull));         // executed tokens before token tid
+    for (int v = 0; v < wave; ++v) before += __popcll(smask[v]);
+    const int count = __popcll(smask[0]) + __popcll(smask[1]) + __popcll(smask[2]) + __popcll(smask[3]);
+    if (tid < T) spre[tid] = static_cast<uint32_t>(before);
+    if (tid == 0) spre[T] = static_cast<uint32_t>(count);
+    if (exec && before == static_cast<int>(blockIdx.x)) srow = tid; // the row this workgroup normalises
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (tid == 0) {
+            *a.s.count = count;
+            if (a.s.count_copy) *a.s.count_copy = count;
+        }
+        if (exec) {
+            const int pos = before;
+            a.s.idx[pos] = tid;
+            if (a.s.idx_copy) a.s.idx_copy[pos] = tid;
+            if (a.s.row_seq) {
+                int lo = 0, hi = a.s.B;                             // last b with seq_offsets[b] <= t
+                while (lo + 1 < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (a.s.seq_offsets[mid] <= tid) lo = mid; else hi = mid;
+                }
+                a.s.row_seq[pos] = lo;
+            }
+        }
+        for (int b = tid; b <= a.s.B; b += 256) {
+            const int o = a.s.seq_offsets[b];
+            if (a.s.cu_exec) a.s.cu_exec[b] = o >= T ? count : static_cast<int>(spre[o]);
+        }
+        if (a.s.kv_len) {
+            for (int b = tid; b < a.s.B; b += 256) {
+                const int o0 = a.s.seq_offsets[b], o1 = a.s.seq_offsets[b + 1];
+                const int n = (o1 >= T ? count : static_cast<int>(spre[o1])) - (o0 >= T ? count : static_cast<int>(spre[o0]));
+                const int old = a.s.kv_len[b];
+                a.s.kv_old[b] = old;
+                a.s.kv_len[b] = a.s.kv_cap > 0 ? min(old + n, max(old, a.s.kv_cap)) : old + n;
+            }
+        }
+    }
+    // 3. this workgroup's compact row
+    const int i = blockIdx.x;
+    if (i >= count) return;
+    const int t = srow;
+    const u32x4_t* xr = reinterpret_cast<const u32x4_t*>(a.x + static_cast<size_t>(t) * H);
+    const u32x4_t* gr = reinterpret_cast<const u32x4_t*>(a.gain);
+    u32x4_t* orow = reinterpret_cast<u32x4_t*>(a.out + static_cast<size_t>(i) * H);
+    constexpr int KEEP = 4;
+    u32x4_t keep[KEEP];
+    float ss = 0.0f;
+    auto sumsq = [&](const u32x4_t& v) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = act_to_float<BF16>(static_cast<uint16_t>(v[j] & 0xffffu));
+            const float q = act_to_float<BF16>(static_cast<uint16_t>(v[j] >> 16));
+            ss = fmaf(p, p, ss);
+            ss = fmaf(q, q, ss);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = tid + u * 256;
+        keep[u] = c < chunks ? xr[c] : u32x4_t{0u, 0u, 0u, 0u};
+        sumsq(keep[u]);
+    }
+    for (int c = tid + KEEP * 256; c < chunks; c += 256) sumsq(xr[c]);
+    ss = wave_sum(ss);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float inv = 1.0f / sqrtf(ss / static_cast<float>(H) + a.eps);
+    auto emit = [&](int c, const u32x4_t& v) {
+        const u32x4_t g = gr[c];
+        u32x4_t o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = act_to_float<BF16>(static_cast<uint16_t>(v[j] & 0xffffu)) * inv *
+                            act_to_float<BF16>(static_cast<uint16_t>(g[j] & 0xffffu));
+            const float q = act_to_float<BF16>(static_cast<uint16_t>(v[j] >> 16)) * inv *
+                            act_to_float<BF16>(static_cast<uint16_t>(g[j] >> 16));
+            o[j] = static_cast<uint32_t>(float_to_half_bits(p)) | (static_cast<uint32_t>(float_to_half_bits(q)) << 16);
+        }
+        orow[c] = o;
+    };
+#pragma unroll
+    for (int u = 0; u < KEEP; ++u) {
+        const int c = tid + u * 256;
+        if (c < chunks) emit(c, keep[u]);
+    }
+    for (int c = tid + KEEP * 256; c < chunks; c += 256) emit(c, xr[c]);
+}
+
+bool fused_select_norm_fits(int T, int max_rows) { return max_rows > 0 && T <= kFusedMaxT; }
+
+hipError_t launch_select_norm(const void* x, int bf16, int H, const float* z, const void* gain, float eps, void* out_f16,
+                              const SelectArgs& s, int max_rows, hipStream_t stream) {
+    FusedArgs a{};
+    a.x = reinterpret_cast<const uint16_t*>(x); a.H = H; a.z = z;
+    a.gain = reinterpret_cast<const uint16_t*>(gain); a.eps = eps;
+    a.out = reinterpret_cast<uint16_t*>(out_f16); a.s = s;
+    if (bf16) hipLaunchKernelGGL(select_norm_kernel<true>, dim3(max_rows), dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(select_norm_kernel<false>, dim3(max_rows), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
 // Threshold calibration (Sec. 3.4): for fixed scores, how many (layer, token) pairs would execute at each of
 // the grid thresholds.  zthr[j] ascends with j; a score falls into bin b = number of thresholds it reaches,
 // so the count at threshold j is the sum of bins j+1 .. NTHR.  Integer atomics only: deterministic.

@@ -83,6 +83,27 @@ def test_layer_with_large_attention_logits(qt, std, d):
     _check_layer(qt, shape, 700, [700], "ratio", 1.0, seed=31, std=std)
 
 
+@pytest.mark.parametrize("mode,val", [("ratio", 0.5), ("ratio", 0.3), ("threshold", 0.5)])
+def test_small_call_with_tied_scores(qt, mode, val):
+    # a call small enough for the single-launch router + selection + normalisation kernel, with every hidden row
+    # present three times (in different sequences and at different positions): the scores tie in threes, the ratio rule
+    # must cut through a tie towards the lower token index, the threshold rule takes all of a tie or none
+    shape = si.LayerShape(256, 4, 2, 64, 688, 4, 32, "bf16")
+    tensors = si.layer_tensors(shape, 0, 33, unit_gains=False, std=0.08)
+    base = si.hidden_states(shape, 50, 33)
+    x = torch.cat([base, base, base], dim=0)
+    T = x.shape[0]
+    offs, pos = si.ragged_sequences([70, 0, 45, 35], [0, 3, 11, 200])
+    got, idx, _ = _run_layer(qt, shape, tensors, x, offs, pos, mode, val)
+    p, _ = oracle_layer(shape, 0, 33, tensors=tensors)
+    want, widx, z = orc.layer_forward(to_f64(x), p, cfg_dict(shape), offs.numpy(), pos.numpy(), mode, val)
+    assert np.array_equal(z[:50].view(np.uint32), z[50:100].view(np.uint32))      # the ties are real
+    assert np.array_equal(idx, widx)
+    skipped = np.setdiff1d(np.arange(T), widx)
+    assert torch.equal(got[skipped], x[skipped])
+    check_parity(orc.parity_error(to_f64(got)[widx], want[widx]), shape.act_dtype, ("tied scores", mode, val), hidden=shape.hidden)
+
+
 def test_layer_spans_several_row_tiles(qt):
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "fp16")
     _check_layer(qt, shape, 700, [300, 400], "ratio", 0.8, seed=2, std=0.08)
