@@ -23,7 +23,38 @@ struct GemmDev {
     int bits;                      // 4, 3 or 2: width of the weight codes
     int ksplit;                    // decode kernel: parts K is cut into across workgroups (1 = none)
     int epi_rt;                    // decode kernel: epilogue chosen at run time (GemmEpilogue)
+    int tail;                      // 0: all rows; 1: all but gemm_tail_rows(); 2: only those last rows (small-row kernels)
+    int M_full;                    // tail == 2: host bound on the row count of the whole matrix (M_max bounds the tail)
+    int tail_tiles_n, tail_slots;  // tail != 0: column tiles of the 128-row-tile launch, workgroups the chip holds
 };
+
+// Rows the 128-row-tile kernel hands to the small-row kernels.  A last row tile that is at most half full still costs
+// every workgroup of its row a whole tile time, and when the tile count without it is what the chip holds in whole
+// rounds it adds an extra round (measured on the 7B-shaped layer, 4115 instead of 4096 rows: down-proj 0.34 -> 0.46
+// ms); the same rows as a separate small-row launch cost 12-45 us.  So: a remainder of at most 64 rows always goes
+// to the small-row kernels, a larger one only when leaving it out saves a round.  Both launches evaluate this on the
+// device-side count with the same tiles_n and slots.
+__host__ __device__ inline int gemm_tail_rows(int M, int tiles_n, int slots) {
+    const int rem = M & 127, full = M >> 7;
+    if (full == 0 || rem == 0) return 0;
+    if (rem <= 64) return rem;
+    return ((full + 1) * tiles_n + slots - 1) / slots > (full * tiles_n + slots - 1) / slots ? rem : 0;
+}
+
+// Small-row kernels: first row and row count of this workgroup's chunk.  chunk_row0 is the start of its chunk inside
+// the rows the launch covers: the whole matrix, or (tail launch) the rows after the last full 128-row tile.
+__device__ __forceinline__ bool gemm_chunk_rows(const GemmDev& p, int chunk_row0, int rows_per_chunk, int& row0, int& M) {
+    if (p.tail == 2) {
+        const int full = p.count ? min(*p.count, p.M_full) : p.M_full;
+        const int t = gemm_tail_rows(full, p.tail_tiles_n, p.tail_slots);
+        row0 = full - t + chunk_row0;
+        M = min(t - chunk_row0, rows_per_chunk);
+    } else {
+        row0 = chunk_row0;
+        M = min((p.count ? min(*p.count, p.M_max) : p.M_max) - row0, rows_per_chunk);
+    }
+    return M > 0;
+}
 
 constexpr int kLdsStride = 72;     // halves per LDS row of the A tile (64 + 8 padding)
 

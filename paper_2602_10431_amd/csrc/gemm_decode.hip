@@ -48,11 +48,10 @@ gemm_decode_kernel(GemmDev p) {
     // of one column block get ids 8 apart, so they stream the same weights through the same L2.
     const int within = blockIdx.x % (8 * p.row_chunks);
     const int tile_n = (blockIdx.x / (8 * p.row_chunks)) * 8 + (within & 7);
-    const int row0 = (within >> 3) * 64;
     const int ks = blockIdx.y;
     if (tile_n >= p.tiles_n) return;
-    const int M = min((p.count ? min(*p.count, p.M_max) : p.M_max) - row0, ROWS);
-    if (M <= 0) return;
+    int row0, M;
+    if (!gemm_chunk_rows(p, (within >> 3) * 64, ROWS, row0, M)) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % NWN, wk = wave / NWN;

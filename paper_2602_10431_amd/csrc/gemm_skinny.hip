@@ -39,10 +39,9 @@ gemm_skinny_kernel(GemmDev p) {
     // they run on the same XCD right after each other and the second one finds the weights in that L2.
     const int within = blockIdx.x % (8 * p.row_chunks);
     const int tile_n = (blockIdx.x / (8 * p.row_chunks)) * 8 + (within & 7);
-    const int row0 = (within >> 3) * 64;
     if (tile_n >= p.tiles_n) return;
-    const int M = min((p.count ? min(*p.count, p.M_max) : p.M_max) - row0, ROWS);
-    if (M <= 0) return;
+    int row0, M;
+    if (!gemm_chunk_rows(p, (within >> 3) * 64, ROWS, row0, M)) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;

@@ -47,7 +47,8 @@ gemm_w4a16_kernel(GemmDev p) {
     // cores, the bottleneck: +31 % at half the rows).  Consecutive tiles run down the rows of one column
     // panel, and with a grid that is a multiple of 8 a workgroup stays on the row tiles congruent to its
     // XCD, so an XCD's L2 keeps seeing the same few A panels.
-    const int M = p.count ? min(*p.count, p.M_max) : p.M_max;
+    int M = p.count ? min(*p.count, p.M_max) : p.M_max;
+    if (p.tail == 1) M -= gemm_tail_rows(M, p.tail_tiles_n, p.tail_slots);                    // those rows go to a small-row launch
     const int live_m = (M + BM - 1) / BM;
     const int n_tiles = live_m * p.tiles_n;
 
@@ -272,7 +273,8 @@ template <int BITS, int WM, int WN, int FM, int FN, int GPT, int EPI, int OCC>
 static hipError_t launch_cfg(GemmDev& d, hipStream_t stream) {
     constexpr int BM = WM * FM * 32;
     constexpr int BNF = WN * FN;
-    d.tiles_m = (d.M_max + BM - 1) / BM;
+    const int rows = (d.tail == 1 && d.rows_exact) ? d.M_max - gemm_tail_rows(d.M_max, d.tail_tiles_n, d.tail_slots) : d.M_max;
+    d.tiles_m = (rows + BM - 1) / BM;
     d.tiles_n = (d.vf_total + BNF - 1) / BNF;
     // exact row count: one workgroup per tile, scheduled by the hardware as slots free up; a host bound that
     // may be far above the device-side count: as many workgroups as fit on the chip, each walking its tiles
@@ -306,6 +308,28 @@ static hipError_t launch_gpt(GemmDev& d, int epi, hipStream_t stream) {
         case EPI_SWIGLU_F16: return launch_epi<BITS, GPT, EPI_SWIGLU_F16>(d, stream);
         default: return launch_epi<BITS, GPT, EPI_RESID_SCATTER>(d, stream);
     }
+}
+
+// At most 64 rows (a decode step, or the last rows of a prefill call): one-fragment waves that share activation tiles;
+// hidden-size-wide outputs (o-proj, down-proj) also cut K across workgroups when the caller can add the partial tiles.
+static hipError_t launch_small_rows(GemmDev& d, const GemmArgs& a, bool parts_ok, hipStream_t stream) {
+    const bool resid = a.epilogue == EPI_RESID_F32 || a.epilogue == EPI_RESID_SCATTER;
+    // (measured, 7B shape at 64 rows: the 12288-column q|k|v output, whose 192 two-fragment blocks nearly fill the
+    // chip without cutting K, takes 17.6 us on the K-sliced skinny kernel and 20.3 us on the decode kernel)
+    const bool wide_store = a.epilogue == EPI_STORE_F16 && d.M_max > 32 && d.vf_total >= 256;
+    if (!resid && !wide_store) {
+        int nwn;
+        gemm_decode_plan(d, a.epilogue, 1, &nwn);
+        return launch_gemm_decode(d, a.epilogue, nwn, 1, stream);
+    }
+    if (parts_ok && a.part && a.n_parts) {
+        int nwn;
+        const int split = gemm_decode_plan(d, EPI_PARTIAL_F32, kGemmPartMax, &nwn);
+        d.out = a.part;
+        *a.n_parts = split;
+        return launch_gemm_decode(d, EPI_PARTIAL_F32, nwn, split, stream);
+    }
+    return launch_gemm_skinny(d, a.epilogue, stream);
 }
 
 hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
@@ -343,26 +367,7 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
     // chunk per workgroup (measured on 13B-shaped linears at 128 rows: 26-59 us against 64-178 us here; at 256
     // rows the two are level).
     if (a.n_parts) *a.n_parts = 0;
-    if (d.M_max <= kGemmPartRows) {
-        // decode steps: one-fragment waves that share activation tiles; hidden-size-wide outputs (o-proj, down-proj)
-        // also cut K across workgroups when the caller can add the partial tiles
-        const bool resid = a.epilogue == EPI_RESID_F32 || a.epilogue == EPI_RESID_SCATTER;
-        // (measured, 7B shape at 64 rows: the 12288-column q|k|v output, whose 192 two-fragment blocks nearly fill the
-        // chip without cutting K, takes 17.6 us on the K-sliced skinny kernel and 20.3 us on the decode kernel)
-        const bool wide_store = a.epilogue == EPI_STORE_F16 && d.M_max > 32 && d.vf_total >= 256;
-        if (!resid && !wide_store) {
-            int nwn;
-            gemm_decode_plan(d, a.epilogue, 1, &nwn);
-            return launch_gemm_decode(d, a.epilogue, nwn, 1, stream);
-        }
-        if (a.part && a.n_parts) {
-            int nwn;
-            const int split = gemm_decode_plan(d, EPI_PARTIAL_F32, kGemmPartMax, &nwn);
-            d.out = a.part;
-            *a.n_parts = split;
-            return launch_gemm_decode(d, EPI_PARTIAL_F32, nwn, split, stream);
-        }
-    }
+    if (d.M_max <= kGemmPartRows) return launch_small_rows(d, a, true, stream);
     if (d.M_max <= 256) return launch_gemm_skinny(d, a.epilogue, stream);
     // A few hundred rows: so few 128 x 256 tiles that a CU holds at most one workgroup, whose k-loop then runs
     // at one memory latency per k-tile.  The 64-row kernel with its deep prefetch rings takes over while its own
@@ -373,6 +378,21 @@ hipError_t launch_gemm_w4a16(const GemmArgs& a, hipStream_t stream) {
         const int mid_tiles = ((d.M_max + 63) / 64) * ((d.vf_total + (swiglu ? 7 : 3)) / (swiglu ? 8 : 4));
         const int cus = resident_workgroups(1);
         if (swiglu ? mid_tiles <= 2 * cus : 2 * mid_tiles <= 5 * cus) return launch_gemm_mid(d, a.epilogue, stream);
+    }
+    // 128-row tiles from here on; the rows after the last full tile may go to the small-row kernels (gemm_tail_rows).
+    // With a device-side count (threshold mode) the tail launch is always made and decides on the device.
+    if (d.M_max >= 128) {
+        d.tail_tiles_n = (d.vf_total + 7) / 8;              // launch_epi: 4 waves x 2 fragments per workgroup
+        d.tail_slots = resident_workgroups(2);
+        const int tail_bound = a.rows_exact ? gemm_tail_rows(d.M_max, d.tail_tiles_n, d.tail_slots) : 127;
+        if (tail_bound > 0) {
+            GemmDev t = d;
+            t.tail = 2; t.M_full = d.M_max; t.M_max = tail_bound;
+            const hipError_t e = tail_bound <= kGemmPartRows ? launch_small_rows(t, a, false, stream)
+                                                             : launch_gemm_skinny(t, a.epilogue, stream);
+            if (e != hipSuccess) return e;
+            d.tail = 1;
+        }
     }
     if (a.bits == 3) {
         if (a.group == 32) return launch_gpt<3, 2>(d, a.epilogue, stream);

@@ -77,6 +77,28 @@ def test_llama7b_shaped_prefill_layer_threshold_mode(qt):
     _prefill_case(qt, si.C2, 8, 1024, None, seed=14, threshold=0.4)
 
 
+@pytest.mark.parametrize("rows", [4115, 4196])
+def test_llama7b_shaped_prefill_layer_rows_beyond_the_last_full_tile(qt, rows):
+    # 4115 executed rows = 32 full 128-row tiles + 19 rows: every linear hands those 19 rows to the small-row kernels
+    # (all four epilogues: q|k|v store, o-proj residual, gate/up SwiGLU, down-proj residual + scatter).
+    # 4196 = 32 tiles + 100 rows: only the linears whose 33rd row of tiles would start another round of workgroups do
+    # (q|k|v, o-proj, down-proj on a 256-CU chip; gate/up keeps its 33rd tile row), in two 64-row chunks
+    ratio = rows / 8192
+    assert orc.executed_count(ratio, 8192) == rows
+    _prefill_case(qt, si.C2, 8, 1024, ratio, seed=18)
+
+
+def test_llama7b_shaped_prefill_layer_threshold_mode_split_decided_on_device(qt):
+    # threshold mode with a count that leaves 1..64 rows beyond the last full 128-row tile: the count exists on the
+    # device only, so both the tiled launch and the small-row launch take the split decision from it
+    shape, T, seed = si.C2, 8192, 19
+    x = si.hidden_states(shape, T, seed)
+    z = orc.router_scores(to_f64(x), si.layer_tensors(shape, 0, seed, unit_gains=True)["router_w"].numpy(), 0.0)
+    theta = next(th for th in (0.40 + 0.0005 * i for i in range(400))
+                 if 1 <= len(orc.select_threshold(z, th)) % 128 <= 64 and len(orc.select_threshold(z, th)) > 2000)
+    _prefill_case(qt, shape, 8, 1024, None, seed=seed, threshold=theta)
+
+
 def test_llama7b_shaped_prefill_layer_three_bit(qt):
     import dataclasses
     _prefill_case(qt, dataclasses.replace(si.C2, bits=3), 8, 1024, 0.5, seed=15)
