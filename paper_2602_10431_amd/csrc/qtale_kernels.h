@@ -102,7 +102,7 @@ struct GemmArgs {
     const void* A;             // [M][K] fp16
     const int32_t* count;      // device row count (nullable: use M_max)
     int M_max;                 // host upper bound of rows
-    int rows_exact;            // nonzero: the row count equals M_max (ratio mode), no tile will be empty
+    int rows_exact;            // nonzero: the row count equals M_max (ratio mode); zero: M_max is a bound, the count is read on the device
     int K;
     int group;
     int bits;                  // 4 or 3

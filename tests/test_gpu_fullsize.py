@@ -35,7 +35,7 @@ def _prefill_case(qt, shape, B, S, ratio, seed, threshold=None):
     if threshold is None:
         qt.qtale_set_exec_ratio(ctx, ratio)
     else:
-        qt.qtale_set_threshold(ctx, threshold)                   # count known on the device only: persistent GEMM form
+        qt.qtale_set_threshold(ctx, threshold)                   # count known on the device only
     xg = x.cuda()
     idx = torch.full((T,), -1, dtype=torch.int32, device="cuda")
     cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -73,7 +73,7 @@ def test_llama7b_shaped_prefill_layer_8x1024_bf16_ratio_half(qt):
 
 def test_llama7b_shaped_prefill_layer_threshold_mode(qt):
     # Eq. 9 verbatim at full size: about 62 % of the 8192 tokens execute at theta = 0.4 with these scores; the
-    # GEMMs walk the live tiles with persistent workgroups (more tiles than resident workgroups)
+    # GEMM grids cover all 8192 rows and the workgroups beyond the live tiles leave at once
     _prefill_case(qt, si.C2, 8, 1024, None, seed=14, threshold=0.4)
 
 

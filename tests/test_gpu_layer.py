@@ -120,7 +120,8 @@ def test_layer_with_a_few_hundred_executed_rows(qt, bits, mode, val):
 @pytest.mark.parametrize("mode,val", [("ratio", 1.0), ("threshold", 0.3)])
 def test_layer_on_large_tiles_with_ragged_down_proj(qt, mode, val):
     # hidden 1024 and more than 5120 executed rows: every linear of the layer runs on the 128 x 256 tiles (ratio
-    # mode: one tile per workgroup; threshold mode: persistent workgroups), the down-proj with K = 1384
+    # mode: a grid of exactly the live tiles; threshold mode: a grid for the host bound, the live tile count read on
+    # the device), the down-proj with K = 1384
     shape = si.LayerShape(1024, 8, 8, 128, 1384, 4, 128, "bf16")
     _check_layer(qt, shape, 5600, [2700, 2900], mode, val, seed=40, std=0.04)
 
@@ -169,8 +170,8 @@ def test_layer_with_two_output_mlp_router(qt, mode, val):
 
 
 def test_threshold_mode_with_more_tiles_than_resident_workgroups(qt):
-    # 12800 rows x (2 x 688) gate/up columns = 600 tiles of 128 x 256: every persistent workgroup walks several
-    # tiles; theta = 0.35 keeps most rows, so the live tile count is only known on the device
+    # 12800 rows x (2 x 688) gate/up columns = 600 tiles of 128 x 256, more than the chip holds at once; theta = 0.35
+    # keeps most rows, and the live tile count is only known on the device
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "bf16")
     _check_layer(qt, shape, 12800, [1280] * 10, "threshold", 0.35, seed=24, std=0.08)
 
