@@ -576,6 +576,13 @@ def main():
         others = {}
         l8 = quantized_stack(qt, si, torch, si.C4, 32)
         others["configs[3]"] = prefill_section(qt, si, torch, si.C4, l8, 4, 4096, (0.6, 1.0), "configs[3]", steps=2)
+        # a call of 32768 tokens: the selection kernel (one workgroup for any T) no longer holds its keys on chip
+        # beyond 16384 tokens; its share of a layer at this size, from HIP events over two layers
+        long_call = prefill_section(qt, si, torch, si.C4, l8[:2], 8, 4096, (0.6,), "configs[3] shape, 8 x 4096", steps=1)
+        ms = long_call["by_exec_ratio"]["0.6"]["kernel_ms_per_launch"]
+        others["select_kernel_at_32768_tokens"] = {"workload": long_call["workload"], "select_ms": ms["select"],
+                                                   "layer_ms": sum(ms.values()),
+                                                   "share_of_layer": ms["select"] / sum(ms.values())}
         del l8
         torch.cuda.empty_cache()
         l13 = quantized_stack(qt, si, torch, si.C5, 40)

@@ -28,16 +28,15 @@ struct GemmDev {
     int tail_tiles_n, tail_slots;  // tail != 0: column tiles of the 128-row-tile launch, workgroups the chip holds
 };
 
-// Rows the 128-row-tile kernel hands to the small-row kernels.  A last row tile that is at most half full still costs
-// every workgroup of its row a whole tile time, and when the tile count without it is what the chip holds in whole
-// rounds it adds an extra round (measured on the 7B-shaped layer, 4115 instead of 4096 rows: down-proj 0.34 -> 0.46
-// ms); the same rows as a separate small-row launch cost 12-45 us.  So: a remainder of at most 64 rows always goes
-// to the small-row kernels, a larger one only when leaving it out saves a round.  Both launches evaluate this on the
-// device-side count with the same tiles_n and slots.
+// Rows the 128-row-tile kernel hands to the small-row kernels: the rows after the last full tile, when leaving their
+// row of tiles out saves the launch a whole round of workgroups (tile count / workgroups the chip holds, rounded up).
+// Measured on the 7B-shaped layer at 4115 instead of 4096 rows (33 x 16 tiles on 512 slots): down-proj 0.47 -> 0.37
+// ms, o-proj 0.20 -> 0.17 ms with the 19 rows as a separate small-row launch; where no round is saved the same split
+// costs 10-30 us per linear, so it is not made.  Both launches evaluate this on the device-side count with the
+// same tiles_n and slots.
 __host__ __device__ inline int gemm_tail_rows(int M, int tiles_n, int slots) {
     const int rem = M & 127, full = M >> 7;
     if (full == 0 || rem == 0) return 0;
-    if (rem <= 64) return rem;
     return ((full + 1) * tiles_n + slots - 1) / slots > (full * tiles_n + slots - 1) / slots ? rem : 0;
 }
 

@@ -79,10 +79,10 @@ def test_llama7b_shaped_prefill_layer_threshold_mode(qt):
 
 @pytest.mark.parametrize("rows", [4115, 4196])
 def test_llama7b_shaped_prefill_layer_rows_beyond_the_last_full_tile(qt, rows):
-    # 4115 executed rows = 32 full 128-row tiles + 19 rows: every linear hands those 19 rows to the small-row kernels
-    # (all four epilogues: q|k|v store, o-proj residual, gate/up SwiGLU, down-proj residual + scatter).
-    # 4196 = 32 tiles + 100 rows: only the linears whose 33rd row of tiles would start another round of workgroups do
-    # (q|k|v, o-proj, down-proj on a 256-CU chip; gate/up keeps its 33rd tile row), in two 64-row chunks
+    # 4115 executed rows = 32 full 128-row tiles + 19 rows, 4196 = 32 tiles + 100 rows: the linears whose 33rd row of
+    # tiles would start another round of workgroups on a 256-CU chip (q|k|v, o-proj with its residual, down-proj with
+    # residual + scatter) hand those rows to the small-row kernels, as one chunk or as two 64-row chunks; gate/up keeps
+    # its 33rd tile row
     ratio = rows / 8192
     assert orc.executed_count(ratio, 8192) == rows
     _prefill_case(qt, si.C2, 8, 1024, ratio, seed=18)

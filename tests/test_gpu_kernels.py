@@ -242,6 +242,32 @@ def test_large_tile_swiglu_short_and_ragged_k(qt, K, G, bits):
     check_parity(orc.parity_error(out.cpu().to(torch.float64).numpy(), want), "fp16", "w4a16 gemm")
 
 
+@pytest.mark.parametrize("M", [2088, 2148])
+@pytest.mark.parametrize("bits", [4, 3])
+def test_large_tile_gemm_rows_beyond_the_last_full_tile(qt, M, bits):
+    # 16 full 128-row tiles + 40 (or 100) rows on outputs of 32 column tiles: the 17th row of tiles would be tiles
+    # 513..544 on a chip that holds 512 workgroups, so those rows run on the small-row kernels instead (one chunk, two
+    # 64-row chunks); plain store and SwiGLU epilogues
+    K, G = 256, 128
+    g = torch.Generator().manual_seed(M + bits)
+    A = torch.randn(M, K, generator=g).to(torch.float16)
+    A64 = A.to(torch.float64).numpy()
+    W = torch.randn(8192, K, generator=g) * 0.05
+    out = qt.qtale_linear_w4a16(qt.qtale_quantize(W.cuda(), bits, G), A.cuda())
+    torch.cuda.synchronize()
+    want = A64 @ orc.dequantize(*orc.quantize_rtn(W.numpy(), bits, G), G).T
+    check_parity(orc.parity_error(out.cpu().to(torch.float64).numpy(), want), "fp16", ("w4a16 gemm", M, bits))
+    assert orc.parity_error(out[-(M % 128):].cpu().to(torch.float64).numpy(), want[-(M % 128):]) < 2e-2
+    Wg, Wu = torch.randn(4096, K, generator=g) * 0.05, torch.randn(4096, K, generator=g) * 0.05
+    out = qt.qtale_swiglu_w4a16(qt.qtale_quantize(Wg.cuda(), bits, G), qt.qtale_quantize(Wu.cuda(), bits, G), A.cuda())
+    torch.cuda.synchronize()
+    dg = orc.dequantize(*orc.quantize_rtn(Wg.numpy(), bits, G), G)
+    du = orc.dequantize(*orc.quantize_rtn(Wu.numpy(), bits, G), G)
+    want = orc.silu(A64 @ dg.T) * (A64 @ du.T)
+    check_parity(orc.parity_error(out.cpu().to(torch.float64).numpy(), want), "fp16", ("w4a16 gemm", M, bits))
+    assert orc.parity_error(out[-(M % 128):].cpu().to(torch.float64).numpy(), want[-(M % 128):]) < 2e-2
+
+
 def test_linear_random_shape_sweep(qt):
     # 40 seeded shapes across the dispatch regimes (few rows / 64-row chunks / 64-row tiles / 128-row tiles), ragged K, output
     # widths that are not multiples of the 32-column fragment, all code widths and group sizes
