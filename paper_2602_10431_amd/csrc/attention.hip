@@ -50,21 +50,37 @@ flash_prefill_kernel(AttnDev p) {
     constexpr int KS = D / 16;          // k-steps of the QK^T product
     constexpr int DF = D / 32;          // 32-wide fragments of the head dimension
     constexpr int KSTR = D + 8;         // LDS row stride of the K tile (halves)
-    constexpr int VSTR = 64 + 4;        // LDS row stride of the transposed V tile (halves)
+    // Transposed V tile Vt[column][key]: 64 keys + room for the column skew, row stride 42 dwords (16 lanes that read
+    // 8 bytes of consecutive rows hit 16 different bank pairs).  A thread stores 4 keys (8 bytes) of 8 columns; the
+    // 16 lanes that hold the same keys and 16 different column chunks dc would land on two bank pairs, so the key
+    // group index is XOR-ed with dc >> 2 (uniform per 32-column fragment on the read side) and rows with bit 1 of dc
+    // set are shifted by 8 dwords: bits 1-2, 3 and 4 of the bank index then come from dc >> 2, dc bit 1 and dc bit 0.
+    constexpr int VSTR = 64 + 16 + 4;   // LDS row stride of the transposed V tile (halves)
     constexpr int CPR = D / 8;          // 16-byte chunks per K/V row
     constexpr int CH = (64 * CPR) / 256;     // K chunks per thread per tile
     constexpr int VG = (16 * CPR + 255) / 256;   // V groups (4 keys x 8 columns) per thread per tile
+    constexpr int kSwShift = CPR == 8 ? 1 : 0;   // 8 chunks per row: two key groups share 16 lanes, swizzle bit 1 instead of bit 0
     __shared__ __attribute__((aligned(16))) half_t Ks2[2][64 * KSTR];    // double-buffered tiles
     __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VSTR];
 
-    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Logical index L = head *
-    // items_max + item is laid out so that every XCD gets one contiguous range of L: the query tiles of one
-    // (sequence, head) read the same keys and values and now run on the same XCD at the same time, so its L2
-    // serves all but the first of them (each pair used to be fetched once per query tile from the fabric).
-    const int per_xcd = gridDim.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int h = L / p.items_max;
-    const int item = L - h * p.items_max;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Every XCD gets a contiguous group of
+    // heads (all query heads of a few key/value heads) and walks the work items in list order, the heads of the group
+    // innermost: the list is sorted by length, longest first, so an XCD's 64 workgroup slots drain evenly (with the
+    // heads outermost the long items of the last head started when most of the work was done: about a third of the
+    // kernel time at two sequences of 4096 tokens was an idle tail), and the workgroups that run at the same time
+    // belong to a few (sequence, head) pairs and similar key ranges, which the L2 serves.
+    int h, item;
+    if ((p.nh & 7) == 0) {
+        const int hx = p.nh >> 3;                                // heads per XCD; gridDim.x = 8 * hx * items_max
+        const int local = blockIdx.x >> 3;
+        item = local / hx;
+        h = (blockIdx.x & 7) * hx + (local - item * hx);
+    } else {
+        const int per_xcd = gridDim.x >> 3;
+        const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        h = L / p.items_max;
+        item = L - h * p.items_max;
+    }
     if (h >= p.nh) return;
     const int4 it = p.items[item];           // one load tells the workgroup everything (unused slots hold -1)
     const int b = it.x, qt = it.y;
@@ -120,26 +136,37 @@ flash_prefill_kernel(AttnDev p) {
     // global -> register staging of one tile.  K: chunk c is key c / CPR, 8 halves at (c % CPR)*8.
     // V: a thread owns 4 consecutive keys x 8 columns and transposes them in registers, so that the
     // transposed tile Vt[column][key] is written with 8-byte stores.
-    // Two register sets: tile t+1 waits in one while tile t+2 is still in flight into the other.
-    u32x4_t kregs[2][CH], vregs[2][VG][4];
+    // One register set: tile t+1 waits in it while tile t is computed.
+    // Element offsets inside a tile are fixed per thread; a tile adds key0 * kv_stride, and the minimum with the
+    // offset of the same column chunk in the last visible key keeps the (partial) last tile inside the sequence.
+    u32x4_t kregs[CH], vregs[VG][4];
+    uint32_t k_off[CH], k_max[CH], v_off[VG], v_max[VG];            // byte offsets (below 4 GB: 32-bit lane offsets on a uniform base)
+    const uint32_t row_bytes = static_cast<uint32_t>(kv_stride) * 2u;
+    const uint32_t last_row = static_cast<uint32_t>(n_keys - 1) * row_bytes;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const int c = i * 256 + tid;
+        k_off[i] = static_cast<uint32_t>(c / CPR) * row_bytes + (c % CPR) * 16;
+        k_max[i] = last_row + (c % CPR) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < VG; ++i) {
+        const int g = min(i * 256 + tid, 16 * CPR - 1);
+        v_off[i] = static_cast<uint32_t>(4 * (g / CPR)) * row_bytes + (g % CPR) * 16;
+        v_max[i] = last_row + (g % CPR) * 16;
+    }
+    const char* kbytes = reinterpret_cast<const char*>(kbase);
+    const char* vbytes = reinterpret_cast<const char*>(vbase);
     auto fetch = [&](int tile, u32x4_t* kreg, u32x4_t (*vreg)[4]) {
-        const int key0 = tile * 64;
+        const uint32_t t_off = static_cast<uint32_t>(tile * 64) * row_bytes;
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = i * 256 + tid;
-            const int key = min(key0 + c / CPR, n_keys - 1);
-            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + static_cast<size_t>(key) * kv_stride + (c % CPR) * 8);
-        }
+        for (int i = 0; i < CH; ++i)
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbytes + min(k_off[i] + t_off, k_max[i]));
 #pragma unroll
-        for (int i = 0; i < VG; ++i) {
-            const int g = min(i * 256 + tid, 16 * CPR - 1);
-            const int kg = g / CPR, dc = g % CPR;
+        for (int i = 0; i < VG; ++i)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int key = min(key0 + 4 * kg + u, n_keys - 1);
-                vreg[i][u] = *reinterpret_cast<const u32x4_t*>(vbase + static_cast<size_t>(key) * kv_stride + dc * 8);
-            }
-        }
+            for (int u = 0; u < 4; ++u)
+                vreg[i][u] = *reinterpret_cast<const u32x4_t*>(vbytes + min(v_off[i] + t_off + static_cast<uint32_t>(u) * row_bytes, v_max[i]));
     };
     auto stage = [&](int buf, const u32x4_t* kreg, const u32x4_t (*vreg)[4]) {
         half_t* Ks = Ks2[buf];
@@ -154,6 +181,7 @@ flash_prefill_kernel(AttnDev p) {
             const int g = i * 256 + tid;
             if (g >= 16 * CPR) continue;
             const int kg = g / CPR, dc = g % CPR;
+            const int vcol = 4 * (kg ^ ((dc >> 2) << kSwShift)) + 16 * ((dc >> 1) & 1);
 #pragma unroll
             for (int w = 0; w < 4; ++w) {                        // word w holds columns 2w, 2w+1 of each key
                 const uint32_t a0 = vreg[i][0][w], a1 = vreg[i][1][w], a2 = vreg[i][2][w], a3 = vreg[i][3][w];
@@ -162,38 +190,46 @@ flash_prefill_kernel(AttnDev p) {
                 even.y = (a2 & 0xffffu) | (a3 << 16);
                 odd.x = (a0 >> 16) | (a1 & 0xffff0000u);
                 odd.y = (a2 >> 16) | (a3 & 0xffff0000u);
-                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w) * VSTR + 4 * kg]) = even;
-                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w + 1) * VSTR + 4 * kg]) = odd;
+                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w) * VSTR + vcol]) = even;
+                *reinterpret_cast<uint2*>(&Vt[(dc * 8 + 2 * w + 1) * VSTR + vcol]) = odd;
             }
         }
     };
 
-    // Tile t+1 is parked in the other LDS buffer and tile t+3 requested before tile t is computed (tile t+2 is
-    // already on its way): one barrier per tile, two tile times to cover the latency of a fetch, and the
-    // staging of one wave overlaps the MFMAs of the others.
-    fetch(0, kregs[0], vregs[0]);
-    stage(0, kregs[0], vregs[0]);
-    if (n_tiles > 1) fetch(1, kregs[1], vregs[1]);
-    if (n_tiles > 2) fetch(2, kregs[0], vregs[0]);
+    // Tile t+1 is parked in the other LDS buffer and tile t+2 requested before tile t is computed: one barrier per
+    // tile, a whole tile time to cover the latency of a fetch, and the staging of one wave overlaps the MFMAs of the
+    // others.
+    fetch(0, kregs, vregs);
+    stage(0, kregs, vregs);
+    if (n_tiles > 1) fetch(1, kregs, vregs);
     __syncthreads();
-    auto tile_step = [&](int tile, u32x4_t* kreg, u32x4_t (*vreg)[4]) {   // kreg/vreg: the set that holds tile + 1
-        if (tile + 1 < n_tiles) stage((tile + 1) & 1, kreg, vreg);
-        if (tile + 3 < n_tiles) fetch(tile + 3, kreg, vreg);
+    // this lane's row of a V^T fragment: row l32, shifted by the row's skew; key group lhi (v_rd0) or 1 - lhi (v_rd1:
+    // fragments whose swizzle flips bit 0 of the key group)
+    const int v_row = l32 * VSTR + 16 * ((l32 >> 4) & 1);
+    const int v_rd0 = v_row + 4 * lhi, v_rd1 = v_row + 4 * (1 - lhi);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        if (tile + 1 < n_tiles) stage((tile + 1) & 1, kregs, vregs);
+        if (tile + 2 < n_tiles) fetch(tile + 2, kregs, vregs);
         const half_t* Ks = Ks2[tile & 1];
         const half_t* Vt = Vt2[tile & 1];
         const int key0 = tile * 64;
         if (key0 < wave_hi) {
             // S^T = K Q^T : rows = keys (two 32-key fragments), column = this lane's query
+            // (the fragments of the whole tile are named before the MFMAs so that the compiler may issue their reads as
+            // early as registers allow)
             float16_t st[2];
+            half8_t ka[2][KS];
+#pragma unroll
+            for (int kf = 0; kf < 2; ++kf)
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    ka[kf][s] = *reinterpret_cast<const half8_t*>(&Ks[(kf * 32 + l32) * KSTR + 16 * s + 8 * lhi]);
 #pragma unroll
             for (int kf = 0; kf < 2; ++kf) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st[kf][r] = 0.0f;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const half8_t ka = *reinterpret_cast<const half8_t*>(&Ks[(kf * 32 + l32) * KSTR + 16 * s + 8 * lhi]);
-                    st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qf[s], st[kf], 0, 0, 0);
-                }
+                for (int s = 0; s < KS; ++s) st[kf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[kf][s], qf[s], st[kf], 0, 0, 0);
             }
             // online softmax over the 32 scores this lane holds (the lane 32 away holds the other 32);
             // only tiles that reach past the wave's smallest causal limit need the mask
@@ -212,18 +248,29 @@ flash_prefill_kernel(AttnDev p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kf][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx * sc);           // running maximum in units of log2 (sc > 0: same arg-max)
+            // Reference point of the exponentials, in units of log2 (sc > 0: same arg-max).  Any value works as long
+            // as numerators and denominator share it, so it only follows the running maximum when some lane's maximum
+            // has grown by more than kLazy (probabilities then stay below 2^kLazy, far inside fp16): with 64 queries
+            // per wave some maximum moves in most tiles, and rescaling the 64 output accumulators every time costs a
+            // fifth of the kernel's vector instructions.
+            constexpr float kLazy = 4.0f;
+            const float m_cand = fmaxf(m_run, mx * sc);
+            const float m_new = __any(m_cand > m_run + kLazy) ? m_cand : m_run;
             float psum = 0.0f;
             half8_t pf[4];
 #pragma unroll
             for (int kf = 0; kf < 2; ++kf)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(st[kf][r], sc, -m_new));
-                    psum += pv;
-                    pf[kf * 2 + (r >> 3)][r & 7] = static_cast<half_t>(pv);
+                for (int r = 0; r < 16; r += 2) {
+                    float2_t pv;
+                    pv[0] = __builtin_amdgcn_exp2f(fmaf(st[kf][r], sc, -m_new));
+                    pv[1] = __builtin_amdgcn_exp2f(fmaf(st[kf][r + 1], sc, -m_new));
+                    psum += pv[0] + pv[1];
+                    const half2_t ph = __builtin_convertvector(pv, half2_t);   // one packed conversion per pair
+                    pf[kf * 2 + (r >> 3)][r & 7] = ph[0];
+                    pf[kf * 2 + (r >> 3)][(r & 7) + 1] = ph[1];
                 }
-            if (__any(m_new != m_run)) {                         // rescale only when some maximum moved
+            if (__any(m_new != m_run)) {                         // rescale only when the reference point moved
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 l_run *= alpha;
 #pragma unroll
@@ -235,25 +282,26 @@ flash_prefill_kernel(AttnDev p) {
             l_run += psum;
             // O^T += V^T P^T : k-step s2 covers keys 16 s2 .. 16 s2 + 15 of the tile; operand element e of a
             // lane is key 16 s2 + 8 (e/4) + 4 (lane/32) + e%4, the order the accumulator layout produced
+            half8_t va[4][DF];
 #pragma unroll
             for (int s2 = 0; s2 < 4; ++s2) {
 #pragma unroll
                 for (int df = 0; df < DF; ++df) {
-                    const half_t* vrow = &Vt[(df * 32 + l32) * VSTR + 16 * s2 + 4 * lhi];
-                    const half4_t v0 = *reinterpret_cast<const half4_t*>(vrow);
-                    const half4_t v1 = *reinterpret_cast<const half4_t*>(vrow + 8);
-                    half8_t va;
-                    va[0] = v0[0]; va[1] = v0[1]; va[2] = v0[2]; va[3] = v0[3];
-                    va[4] = v1[0]; va[5] = v1[1]; va[6] = v1[2]; va[7] = v1[3];
-                    o[df] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pf[s2], o[df], 0, 0, 0);
+                    // key groups 4 s2 + lhi and 4 s2 + 2 + lhi of column df * 32 + l32, at their swizzled places
+                    const int sw = df << kSwShift;               // (dc >> 2) << kSwShift with dc = (df * 32 + l32) >> 3
+                    const half_t* vrow = &Vt[(df * 32) * VSTR] + ((sw & 1) ? v_rd1 : v_rd0);
+                    const half4_t v0 = *reinterpret_cast<const half4_t*>(vrow + 4 * ((4 * s2) ^ (sw & ~1)));
+                    const half4_t v1 = *reinterpret_cast<const half4_t*>(vrow + 4 * ((4 * s2 + 2) ^ (sw & ~1)));
+                    va[s2][df][0] = v0[0]; va[s2][df][1] = v0[1]; va[s2][df][2] = v0[2]; va[s2][df][3] = v0[3];
+                    va[s2][df][4] = v1[0]; va[s2][df][5] = v1[1]; va[s2][df][6] = v1[2]; va[s2][df][7] = v1[3];
                 }
             }
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+                for (int df = 0; df < DF; ++df) o[df] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[s2][df], pf[s2], o[df], 0, 0, 0);
         }
         __syncthreads();
-    };
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        tile_step(tile, kregs[1], vregs[1]);
-        if (tile + 1 < n_tiles) tile_step(tile + 1, kregs[0], vregs[0]);
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -274,10 +322,84 @@ flash_prefill_kernel(AttnDev p) {
 
 // Builds the prefill work list: one item per (sequence, tile of kAttnBQ executed rows), carrying the sequence's
 // first compact row and row count so that the attention workgroups need no further lookups; the slots up to
-// items_max that no tile uses are marked with sequence -1.
+// items_max that no tile uses are marked with sequence -1.  The list is sorted by query tile index, highest
+// first, across all sequences (the tile index is the item's length in keys up to the cached prefix): a counting
+// sort over the tiles-per-sequence histogram.  `levels` is the host bound on tiles per sequence (<= kItemLevels).
+constexpr int kItemLevels = 1024;
+
 __global__ void __launch_bounds__(256)
 attn_items_kernel(const int32_t* __restrict__ cu_exec, int B, int4* __restrict__ items, int items_max,
-                  int32_t* __restrict__ n_items) {
+                  int32_t* __restrict__ n_items, int levels) {
+    __shared__ int cnt[kItemLevels + 1];      // first: sequences with exactly n tiles; then: sequences with more than n
+    __shared__ int offs[kItemLevels + 1];     // items of the tile indices above q
+    __shared__ int fill[kItemLevels + 1];
+    __shared__ int s_total;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i <= levels; i += 256) { cnt[i] = 0; fill[i] = 0; }
+    __syncthreads();
+    for (int b = tid; b < B; b += 256) {
+        const int nt = min((cu_exec[b + 1] - cu_exec[b] + kAttnBQ - 1) / kAttnBQ, levels);
+        atomicAdd(&cnt[nt], 1);
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // two suffix sums over the levels, one wave: lane l owns a chunk of consecutive levels
+        const int chunk = (levels + 64) / 64;
+        const int lo = lane * chunk, hi = min(lo + chunk, levels + 1);
+        int own = 0;
+        for (int n = lo; n < hi; ++n) own += cnt[n];
+        int above = 0;                                           // sum of the chunks of the lanes above
+        {
+            int incl = own;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_down(incl, o, 64);
+                if (lane + o < 64) incl += t;
+            }
+            above = incl - own;
+        }
+        int own2 = 0;
+        for (int n = hi - 1; n >= lo; --n) {
+            const int h = cnt[n];
+            cnt[n] = above;                                      // sequences with more than n tiles
+            own2 += above;
+            above += h;
+        }
+        int above2 = 0;
+        {
+            int incl = own2;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_down(incl, o, 64);
+                if (lane + o < 64) incl += t;
+            }
+            above2 = incl - own2;
+        }
+        for (int n = hi - 1; n >= lo; --n) {
+            offs[n] = above2;                                    // items with a tile index above n
+            above2 += cnt[n];
+        }
+        if (lane == 0) s_total = above2;                         // lane 0 ends below level 0: all items
+    }
+    __syncthreads();
+    for (int b = tid; b < B; b += 256) {
+        const int first = cu_exec[b];
+        const int rows = cu_exec[b + 1] - first;
+        const int nt = min((rows + kAttnBQ - 1) / kAttnBQ, levels);
+        if (nt == 0) continue;
+        const int pos = cnt[nt] + atomicAdd(&fill[nt], 1);        // place among the sequences, most tiles first
+        for (int q = 0; q < nt; ++q) items[offs[q] + pos] = make_int4(b, q, first, rows);
+    }
+    const int used = s_total;
+    for (int i = used + tid; i < items_max; i += 256) items[i] = make_int4(-1, 0, 0, 0);
+    if (tid == 0) *n_items = used;
+}
+
+// The same list for calls whose sequences could have more than kItemLevels query tiles: sequence by sequence, each
+// sequence's tiles longest first.
+__global__ void __launch_bounds__(256)
+attn_items_by_sequence_kernel(const int32_t* __restrict__ cu_exec, int B, int4* __restrict__ items, int items_max,
+                              int32_t* __restrict__ n_items) {
     __shared__ int s_wave[4];
     __shared__ int s_base;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -578,8 +700,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
     }
     const int items_max = (a.max_rows + kAttnBQ - 1) / kAttnBQ + a.B;
     d.items_max = items_max;
-    hipLaunchKernelGGL(attn_items_kernel, dim3(1), dim3(256), 0, stream, a.cu_exec, a.B,
-                       reinterpret_cast<int4*>(a.items), items_max, a.n_items);
+    const int levels = (a.max_rows + kAttnBQ - 1) / kAttnBQ;
+    if (levels <= kItemLevels)
+        hipLaunchKernelGGL(attn_items_kernel, dim3(1), dim3(256), 0, stream, a.cu_exec, a.B,
+                           reinterpret_cast<int4*>(a.items), items_max, a.n_items, levels);
+    else
+        hipLaunchKernelGGL(attn_items_by_sequence_kernel, dim3(1), dim3(256), 0, stream, a.cu_exec, a.B,
+                           reinterpret_cast<int4*>(a.items), items_max, a.n_items);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid(8 * ((items_max * a.nh + 7) / 8)), block(256);

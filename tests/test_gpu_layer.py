@@ -104,6 +104,23 @@ def test_small_call_with_tied_scores(qt, mode, val):
     check_parity(orc.parity_error(to_f64(got)[widx], want[widx]), shape.act_dtype, ("tied scores", mode, val), hidden=shape.hidden)
 
 
+def test_attention_work_list_orders(qt):
+    # the prefill attention work list is sorted by query tile across sequences (counting sort); 700 sequences of very
+    # different lengths (0 to 700 executed tokens, more sequences than the 256 threads that build the list), two key/value
+    # heads shared by four query heads
+    shape = si.LayerShape(256, 4, 2, 64, 688, 4, 32, "bf16")
+    rng = np.random.default_rng(3)
+    lens = [int(v) for v in rng.choice([0, 1, 5, 64, 127, 128, 129, 300, 700], size=700, p=[.1, .2, .2, .2, .1, .05, .05, .05, .05])]
+    _check_layer(qt, shape, sum(lens), lens, "ratio", 0.7, seed=51, std=0.08)
+
+
+def test_attention_work_list_for_very_long_calls(qt):
+    # 131200 executed rows are 1025 query tiles, one more than the sorted work list has levels for: the list is then
+    # built sequence by sequence
+    shape = si.LayerShape(64, 1, 1, 64, 64, 4, 32, "bf16")
+    _check_layer(qt, shape, 131200, [128] * 1025, "ratio", 1.0, seed=52, std=0.15)
+
+
 def test_layer_spans_several_row_tiles(qt):
     shape = si.LayerShape(256, 4, 4, 64, 688, 4, 32, "fp16")
     _check_layer(qt, shape, 700, [300, 400], "ratio", 0.8, seed=2, std=0.08)
