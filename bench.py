@@ -345,6 +345,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="profiling aid: leave the HIP-graph replay leg out of the decode sections")
     ap.add_argument("--decode-only", type=float, default=None, metavar="RATIO",
                     help="profiling aid: run only the decode section at this execution ratio and print its JSON")
+    ap.add_argument("--long-attention", action="store_true",
+                    help="profiling aid: one layer of the stack on 2 x 4096 tokens at ratio 1.0, prints the prefill attention rate")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates FETCH_SIZE/WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -373,6 +375,26 @@ def main():
         layers.append(qt.quantize_layer(t, shape.bits, shape.group, keep_canonical=False))
         del t
     torch.cuda.synchronize()
+    if args.long_attention:
+        Bl, Sl = 2, 4096
+        o2, p2 = si.equal_sequences(Bl, Sl)
+        o2, p2 = o2.to(dev), p2.to(dev)
+        ctx = qt.Context()
+        qt.qtale_set_exec_ratio(ctx, 1.0)
+        xl = si.hidden_states(shape, Bl * Sl, 0, extra=9000, device=dev)
+        for _ in range(2):
+            qt.qtale_layer_forward(ctx, cfg, layers[0], xl.clone(), o2, p2)
+        xr = [xl.clone() for _ in range(5)]
+        qt.qtale_profile_enable(ctx, True)
+        torch.cuda.synchronize()
+        for xi in xr:
+            qt.qtale_layer_forward(ctx, cfg, layers[0], xi, o2, p2)
+        prof = qt.qtale_profile_read(ctx)
+        a_ms = prof["attention"][0] / prof["attention"][1]
+        fl = 4.0 * Sl * Sl / 2 * shape.n_heads * shape.head_dim * Bl
+        print(json.dumps({"long_attention": {"workload": "one layer, 2 x 4096 tokens, ratio 1.0, 32 heads x 128", "attention_ms": a_ms,
+                                             "attention_TFLOPs_causal": fl / (a_ms * 1e-3) / 1e12}}))
+        return
     if args.decode_only is not None:
         print(json.dumps({"decode": decode_section(qt, si, torch, layers, L, ratios=(args.decode_only,), steps=16,
                                                    graph_steps=0 if args.no_graph else 16)}))
