@@ -28,17 +28,20 @@ def pytest_collection_modifyitems(config, items):
 
 
 def pytest_sessionfinish(session, exitstatus):
-    """Writes the parity errors measured in this session (tests/helpers.check_parity), largest first per dtype."""
+    """Writes the parity errors measured in this session (tests/helpers.check_parity), largest first per dtype, to the
+    file named by the environment variable QTALE_PARITY_REPORT."""
     try:
         from tests import helpers
     except Exception:
         return
     if not helpers.OBSERVED:
         return
-    out_dir = os.path.join(ROOT, "gpurun_out")
+    path = os.environ.get("QTALE_PARITY_REPORT")                # file to write; nothing is written without it
+    if not path:
+        return
     try:
-        os.makedirs(out_dir, exist_ok=True)
-        with open(os.path.join(out_dir, "parity_errors.txt"), "w") as f:
+        os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+        with open(path, "w") as f:
             for dt in ("bf16", "fp16"):
                 rows = sorted((r for r in helpers.OBSERVED if r[1] == dt), key=lambda r: -r[2])
                 if rows:

@@ -43,7 +43,7 @@ TINY_GQA = si.LayerShape(hidden=16, n_heads=4, n_kv_heads=2, head_dim=4, inter=2
 # What the kernels deliver is below that: the final rounding to the output dtype alone gives up to 2^-8 (bf16) or
 # 2^-11 (fp16), and the fp16 operands of the four GEMMs and of attention add their share (the maximum is taken over
 # 1e5 to 1e8 elements).  A second, tighter bar at 1.5 to 2 times the largest error measured on the GPU (a full
-# `pytest -m gpu` run writes every measured error to gpurun_out/parity_errors.txt) catches regressions the contract
+# `pytest -m gpu` run with QTALE_PARITY_REPORT=<file> writes every measured error there) catches regressions the contract
 # would let through.  Largest errors measured: single GEMM, fp16 out 3.9e-3; layers with hidden >= 1024: bf16 7.8e-3,
 # fp16 3.7e-3; small layers (hidden 128-512, where one fp16 rounding is a larger share of a short dot product):
 # bf16 1.04e-2, fp16 7.6e-3.
