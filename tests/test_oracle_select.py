@@ -85,6 +85,29 @@ def test_threshold_matches_probability_rule_and_is_monotone():
     np.testing.assert_allclose(orc.execute_probability(z), p)
 
 
+def test_execute_probability_against_the_two_class_softmax_and_closed_forms():
+    # p_0 of Eq. 9 is the class-0 entry of a softmax over the two router outputs; pin the one-argument form against
+    # (a) an explicit, max-shifted softmax over (z_e, z_b) pairs written out here, (b) a library softmax, (c) exact
+    # rational values sigma(ln(a/b)) = a/(a+b), (d) the symmetry p(z) + p(-z) = 1
+    import math
+    from fractions import Fraction
+    import torch
+    rng = np.random.default_rng(9)
+    ze = rng.standard_normal(300) * 4.0
+    zb = rng.standard_normal(300) * 4.0
+    m = np.maximum(ze, zb)
+    soft = np.exp(ze - m) / (np.exp(ze - m) + np.exp(zb - m))
+    got = orc.execute_probability(ze - zb)
+    np.testing.assert_allclose(got, soft, rtol=1e-13)
+    lib = torch.softmax(torch.tensor(np.stack([ze, zb], axis=1)), dim=1)[:, 0].numpy()
+    np.testing.assert_allclose(got, lib, rtol=1e-13)
+    for a, b in [(1, 1), (3, 1), (1, 3), (19, 1), (1, 99), (7, 13)]:
+        assert abs(float(orc.execute_probability(math.log(a / b))) - float(Fraction(a, a + b))) < 1e-15
+    z = rng.standard_normal(100) * 6.0
+    np.testing.assert_allclose(orc.execute_probability(z) + orc.execute_probability(-z), 1.0, rtol=0, atol=1e-15)
+    assert float(orc.execute_probability(0.0)) == 0.5
+
+
 def test_threshold_edges():
     z = _scores(20, 3)
     assert len(orc.select_threshold(z, 0.0)) == 20
