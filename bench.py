@@ -446,7 +446,7 @@ def main():
     achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
     gemm_ms = sum(kern_ms[n] for n in ("qkv_gemm", "o_gemm", "gate_up_gemm", "down_gemm"))
     gemm_flops = 2.0 * k_exec * shape.params_per_layer()
-    roofline = {"bound": "mfma", "kernel": "qtale::gemm_w4a16_kernel<4,1,4,4,2,1,2,2,false,false> (gate/up GEMM with SiLU*up epilogue)",
+    roofline = {"bound": "mfma", "kernel": "qtale::gemm_w4a16_kernel<4,1,4,4,2,1,2,2,false> (gate/up GEMM with SiLU*up epilogue)",
                 "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": recorded_traffic(),
                 "avg_launch_ms": gu_ms, "flops_per_launch": gu_flops,
