@@ -242,13 +242,12 @@ def test_large_tile_swiglu_short_and_ragged_k(qt, K, G, bits):
     check_parity(orc.parity_error(out.cpu().to(torch.float64).numpy(), want), "fp16", "w4a16 gemm")
 
 
-@pytest.mark.parametrize("M", [2088, 2148])
+@pytest.mark.parametrize("M,K,G", [(2088, 256, 128), (2148, 256, 128), (2088, 456, 64)])
 @pytest.mark.parametrize("bits", [4, 3])
-def test_large_tile_gemm_rows_beyond_the_last_full_tile(qt, M, bits):
+def test_large_tile_gemm_rows_beyond_the_last_full_tile(qt, M, K, G, bits):
     # 16 full 128-row tiles + 40 (or 100) rows on outputs of 32 column tiles: the 17th row of tiles would be tiles
     # 513..544 on a chip that holds 512 workgroups, so those rows run on the small-row kernels instead (one chunk, two
-    # 64-row chunks); plain store and SwiGLU epilogues
-    K, G = 256, 128
+    # 64-row chunks); plain store and SwiGLU epilogues; K = 456 is not a multiple of the 64-wide k-tile in either launch
     g = torch.Generator().manual_seed(M + bits)
     A = torch.randn(M, K, generator=g).to(torch.float16)
     A64 = A.to(torch.float64).numpy()
