@@ -182,7 +182,8 @@ def decode_section(qt, si, torch, layers, L, B=64, ctx_len=2048, steps=256, bits
         run(n_prof, True)
         prof = qt.qtale_profile_read(ctx)
         qt.qtale_profile_enable(ctx, False)
-        ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
+        n_layer_calls = prof["attention"][1]            # per layer call: inside a stack the router of layers 1.. is fused away
+        ms = {k: (v[0] / n_layer_calls if n_layer_calls else 0.0) for k, v in prof.items()}
         lin_ms = ms["qkv_gemm"] + ms["o_gemm"] + ms["gate_up_gemm"] + ms["down_gemm"]
         kv_bytes = k_exec * (ctx_len + n_prof / 2.0) * 2 * nkv * d * 2
         res["%.1f" % r] = {"tokens_per_s": B * steps / dt, "ms_per_step": dt * 1e3 / steps,

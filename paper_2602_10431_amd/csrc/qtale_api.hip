@@ -48,6 +48,7 @@ struct Workspace {
     void* act;             // [T][I] fp16
     float* attn_part;      // [min(T, kAttnSplitRows)][nh][kAttnSplitMax][d + 2] fp32: key-range partials of decode attention
     float* gemm_part;      // [kGemmPartMax][min(T, kGemmPartRows)][H] fp32: K-part partial tiles of the decode o-/down-proj
+    int32_t* inv;          // [min(T, 256)] token -> compact row of small calls (-1 = bypassed)
     size_t total;
 };
 
@@ -77,6 +78,7 @@ Workspace carve(const qtale_layer_cfg* c, int T, int B, void* base) {
                                                 kAttnSplitMax * (c->head_dim + 2) * 4));
     w.gemm_part = reinterpret_cast<float*>(take(static_cast<size_t>(kGemmPartMax) * (T < kGemmPartRows ? T : kGemmPartRows) *
                                                 c->hidden * 4));
+    w.inv = reinterpret_cast<int32_t*>(take(static_cast<size_t>(T < 256 ? T : 256) * 4));
     w.total = off;
     return w;
 }
@@ -182,10 +184,19 @@ struct Prof {
         if (e__ != hipSuccess) return QTALE_ERR_HIP;    \
     } while (0)
 
+// How a layer call is linked to its neighbours inside a stack (decode-sized calls only): the previous layer's last
+// kernel may already have written this layer's scores, and this layer's last kernel may write the next layer's.
+struct LayerLink {
+    bool scores_ready = false;                  // in: z of this layer is already in place
+    const qtale_layer_weights* next = nullptr;  // in: the next layer, or null
+    float* next_z = nullptr;                    // in: where its scores go
+    bool next_scored = false;                   // out: they were written
+};
+
 int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_layer_weights* w, void* x, int T,
                        const int32_t* seq_offsets, int B, const int32_t* positions, const qtale_kv* kv,
                        int32_t* sel_idx, int32_t* sel_count, float* scores, const Workspace& ws,
-                       hipStream_t stream) {
+                       hipStream_t stream, LayerLink* link = nullptr) {
     const int bf16 = c->act_dtype == QTALE_ACT_BF16;
     const int H = c->hidden, nh = c->n_heads, nkv = c->n_kv_heads, d = c->head_dim, I = c->inter;
     const int ratio_mode = ctx->mode == QTALE_MODE_RATIO;
@@ -202,7 +213,7 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
     s.idx = ws.idx; s.count = count; s.cu_exec = ws.cu_exec; s.row_seq = ws.row_seq;
     s.kv_len = kv ? kv->kv_len : nullptr; s.kv_old = ws.kv_old; s.kv_cap = kv ? kv->cap : 0;
     s.idx_copy = sel_idx; s.count_copy = sel_count;
-    {
+    if (!(link && link->scores_ready)) {
         Prof pr(ctx, stream, 0);
         if (w->router_hidden > 0)
             HIP_TRY(launch_router_mlp(x, bf16, T, H, w->router_w1, w->router_b1, w->router_w2, w->router_b2,
@@ -210,8 +221,10 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         else
             HIP_TRY(launch_router_score(x, bf16, T, H, w->router_w, w->router_b, z, stream));
     }
-    if (fused_select_norm_fits(T, M_max)) {
+    const bool small_call = fused_select_norm_fits(T, M_max);
+    if (small_call) {
         // decode-sized call: decision, compaction and gather + RMSNorm 1 in one launch
+        s.inv = ws.inv;
         Prof pr(ctx, stream, 1);
         HIP_TRY(launch_select_norm(x, bf16, H, z, w->norm1, c->rms_eps, ws.nbuf, s, M_max, stream));
     } else {
@@ -290,8 +303,15 @@ int layer_forward_impl(qtale_ctx* ctx, const qtale_layer_cfg* c, const qtale_lay
         int d_parts = 0;
         g.part = M_max <= kGemmPartRows ? ws.gemm_part : nullptr; g.n_parts = &d_parts;
         HIP_TRY(launch_gemm_w4a16(g, stream));
-        if (d_parts > 0)
-            HIP_TRY(launch_reduce_scatter(ws.gemm_part, d_parts, ws.h, H, ws.idx, count, M_max, x, bf16, stream));
+        if (d_parts > 0) {
+            if (link && link->next && link->next->router_hidden == 0 && small_call) {
+                HIP_TRY(launch_reduce_scatter_score(ws.gemm_part, d_parts, M_max, ws.h, H, ws.inv, T, x, bf16,
+                                                    link->next->router_w, link->next->router_b, link->next_z, stream));
+                link->next_scored = true;
+            } else {
+                HIP_TRY(launch_reduce_scatter(ws.gemm_part, d_parts, ws.h, H, ws.idx, count, M_max, x, bf16, stream));
+            }
+        }
     }
     return QTALE_OK;
 }
@@ -524,17 +544,25 @@ int qtale_stack_forward(qtale_ctx* ctx, const qtale_layer_cfg* cfg, const qtale_
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const Workspace ws = carve(cfg, T, B, workspace);
     const size_t row_bytes = static_cast<size_t>(cfg->hidden) * 2;
+    bool scores_ready = false;
     for (int l = 0; l < n_layers; ++l) {
         if (dbg_hidden) {
             HIP_TRY(hipMemcpyAsync(reinterpret_cast<char*>(dbg_hidden) + static_cast<size_t>(l) * T * row_bytes, x,
                                    static_cast<size_t>(T) * row_bytes, hipMemcpyDeviceToDevice, s));
         }
+        LayerLink link;
+        link.scores_ready = scores_ready;
+        if (l + 1 < n_layers) {
+            link.next = &layers[l + 1];
+            link.next_z = scores ? scores + static_cast<size_t>(l + 1) * T : ws.z;
+        }
         e = layer_forward_impl(ctx, cfg, &layers[l], x, T, seq_offsets, B, positions,
                                kv_per_layer ? &kv_per_layer[l] : nullptr,
                                sel_idx ? sel_idx + static_cast<size_t>(l) * T : nullptr,
                                sel_count ? sel_count + l : nullptr,
-                               scores ? scores + static_cast<size_t>(l) * T : nullptr, ws, s);
+                               scores ? scores + static_cast<size_t>(l) * T : nullptr, ws, s, &link);
         if (e) return e;
+        scores_ready = link.next_scored;
     }
     return QTALE_OK;
 }

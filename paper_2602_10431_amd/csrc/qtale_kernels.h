@@ -41,6 +41,7 @@ struct SelectArgs {
     int32_t* kv_old;           // [B] out (nullable unless kv_len given): kv_len before the call
     int kv_cap;                // capacity of the cache behind kv_len (0 = unknown): kv_len is not advanced beyond it
     int32_t* idx_copy;         // nullable: second destination for idx (caller-visible output)
+    int32_t* inv;              // nullable (small-call kernel only): [T] compact row of token t, -1 when bypassed
     int32_t* count_copy;       // nullable
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
@@ -51,6 +52,13 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 bool fused_select_norm_fits(int T, int max_rows);
 hipError_t launch_select_norm(const void* x, int bf16, int H, const float* z, const void* gain, float eps, void* out_f16,
                               const SelectArgs& s, int max_rows, hipStream_t stream);
+
+// Decode-sized stacks: the last kernel of layer l (sum of the down-proj's K parts + residual + scatter, Eq. 1 and 3) also
+// scores every token for layer l + 1 (Eq. 2, linear router; the same fp64 summation order as launch_router_score, on the
+// values just stored).  inv [T] is the token -> compact row map of select_norm (-1 = bypassed: the row is only scored).
+hipError_t launch_reduce_scatter_score(const float* part, int n_parts, int part_rows, const float* h, int H, const int32_t* inv,
+                                       int T, void* x, int bf16, const float* w_next, float b_next, float* z_next,
+                                       hipStream_t stream);
 
 // Threshold calibration: bins[b] (kThetaGrid + 1 counters, cleared here) = number of scores that reach exactly
 // b of the kThetaGrid ascending thresholds zthr_dev (device array).

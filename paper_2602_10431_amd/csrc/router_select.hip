@@ -53,6 +53,100 @@ hipError_t launch_router_score(const void* x, int bf16, int T, int H, const floa
     return hipGetLastError();
 }
 
+// Last kernel of a decode-sized layer inside a stack, fused with the next layer's router: one wave per token.  An
+// executed token's row is h + sum of the down-proj's K parts (in part order), rounded to the stream's dtype and stored;
+// a bypassed token's row is read.  Either way the wave then holds the row as stored and accumulates the next layer's
+// score exactly as router_score_kernel does (same chunks per lane, same two fp64 accumulators, same wave sum).
+template <bool BF16>
+__global__ void __launch_bounds__(64)
+scatter_score_kernel(const float* __restrict__ part, int n_parts, size_t part_stride, const float* __restrict__ h, int H,
+                     const int32_t* __restrict__ inv, uint16_t* __restrict__ x, const float* __restrict__ w, float b,
+                     float* __restrict__ z) {
+    const int lane = threadIdx.x;
+    const int t = blockIdx.x;
+    const int row = inv[t];
+    U4* xr = reinterpret_cast<U4*>(x + static_cast<size_t>(t) * H);
+    const float4* wr = reinterpret_cast<const float4*>(w);
+    const float4* hr = reinterpret_cast<const float4*>(h + static_cast<size_t>(row < 0 ? 0 : row) * H);
+    const float4* pr = reinterpret_cast<const float4*>(part + static_cast<size_t>(row < 0 ? 0 : row) * H);
+    const size_t pstep = part_stride / 4;
+    double acc0 = 0.0, acc1 = 0.0;
+    const int chunks = H >> 3;
+    constexpr int U = 4;                                         // chunks whose loads are in flight together
+    for (int c0 = lane; c0 < chunks; c0 += 64 * U) {
+        U4 xv[U];
+        float4 w0[U], w1[U];
+        if (row >= 0) {
+            float4 lo[U], hi[U], pl[U][kGemmPartMax], ph[U][kGemmPartMax];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(c0 + 64 * u, chunks - 1);
+                lo[u] = hr[2 * c]; hi[u] = hr[2 * c + 1];
+                w0[u] = wr[2 * c]; w1[u] = wr[2 * c + 1];
+#pragma unroll
+                for (int s = 0; s < kGemmPartMax; ++s) {
+                    const size_t o = (s < n_parts ? s : 0) * pstep;
+                    pl[u][s] = pr[o + 2 * c];
+                    ph[u][s] = pr[o + 2 * c + 1];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float4 sl = pl[u][0], sh = ph[u][0];
+#pragma unroll
+                for (int s = 1; s < kGemmPartMax; ++s)
+                    if (s < n_parts) {
+                        sl.x += pl[u][s].x; sl.y += pl[u][s].y; sl.z += pl[u][s].z; sl.w += pl[u][s].w;
+                        sh.x += ph[u][s].x; sh.y += ph[u][s].y; sh.z += ph[u][s].z; sh.w += ph[u][s].w;
+                    }
+                const float4 l = lo[u], g = hi[u];
+                const float v[8] = {l.x + sl.x, l.y + sl.y, l.z + sl.z, l.w + sl.w, g.x + sh.x, g.y + sh.y, g.z + sh.z, g.w + sh.w};
+                xv[u].x = static_cast<uint32_t>(float_to_act<BF16>(v[0])) | (static_cast<uint32_t>(float_to_act<BF16>(v[1])) << 16);
+                xv[u].y = static_cast<uint32_t>(float_to_act<BF16>(v[2])) | (static_cast<uint32_t>(float_to_act<BF16>(v[3])) << 16);
+                xv[u].z = static_cast<uint32_t>(float_to_act<BF16>(v[4])) | (static_cast<uint32_t>(float_to_act<BF16>(v[5])) << 16);
+                xv[u].w = static_cast<uint32_t>(float_to_act<BF16>(v[6])) | (static_cast<uint32_t>(float_to_act<BF16>(v[7])) << 16);
+                if (c0 + 64 * u < chunks) xr[c0 + 64 * u] = xv[u];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(c0 + 64 * u, chunks - 1);
+                xv[u] = xr[c];
+                w0[u] = wr[2 * c]; w1[u] = wr[2 * c + 1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (c0 + 64 * u >= chunks) break;
+            const uint32_t xs[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+            const float ws[8] = {w0[u].x, w0[u].y, w0[u].z, w0[u].w, w1[u].x, w1[u].y, w1[u].z, w1[u].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const double a0 = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xs[i] & 0xffffu)));
+                const double a1 = static_cast<double>(act_to_float<BF16>(static_cast<uint16_t>(xs[i] >> 16)));
+                acc0 = fma(a0, static_cast<double>(ws[2 * i]), acc0);
+                acc1 = fma(a1, static_cast<double>(ws[2 * i + 1]), acc1);
+            }
+        }
+    }
+    const double acc = wave_sum(acc0 + acc1);
+    if (lane == 0) z[t] = static_cast<float>(acc + static_cast<double>(b));
+}
+
+hipError_t launch_reduce_scatter_score(const float* part, int n_parts, int part_rows, const float* h, int H, const int32_t* inv,
+                                       int T, void* x, int bf16, const float* w_next, float b_next, float* z_next,
+                                       hipStream_t stream) {
+    if (T == 0) return hipSuccess;
+    const size_t stride = static_cast<size_t>(part_rows) * H;
+    if (bf16)
+        hipLaunchKernelGGL(scatter_score_kernel<true>, dim3(T), dim3(64), 0, stream, part, n_parts, stride, h, H, inv,
+                           reinterpret_cast<uint16_t*>(x), w_next, b_next, z_next);
+    else
+        hipLaunchKernelGGL(scatter_score_kernel<false>, dim3(T), dim3(64), 0, stream, part, n_parts, stride, h, H, inv,
+                           reinterpret_cast<uint16_t*>(x), w_next, b_next, z_next);
+    return hipGetLastError();
+}
+
 // Two-output MLP router (Sec. 2.2: "lightweight MLP" with two outputs; Eq. 9 takes their softmax).  This
 // library's reading: one hidden ReLU layer,  u = relu(W1 x + b1),  (l_e, l_b) = W2 u + b2,  score
 // z = l_e - l_b (the two-class softmax gives p_0 = sigmoid(z)).  All sums in fp64, one rounding to fp32, so
@@ -538,6 +632,7 @@ select_norm_kernel(FusedArgs a) {
             *a.s.count = count;
             if (a.s.count_copy) *a.s.count_copy = count;
         }
+        if (a.s.inv && tid < T) a.s.inv[tid] = exec ? before : -1;
         if (exec) {
             const int pos = before;
             a.s.idx[pos] = tid;
