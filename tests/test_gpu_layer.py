@@ -326,6 +326,40 @@ def test_stack_teacher_forced(qt):
             check_parity(orc.parity_error(to_f64(xout)[widx], want[widx]), shape.act_dtype, ("stack layer", l, mode), hidden=shape.hidden)
 
 
+@pytest.mark.parametrize("dtype,mode,val", [("bf16", "ratio", 0.5), ("fp16", "threshold", 0.45), ("fp16", "ratio", 1.0)])
+def test_decode_sized_stack_equals_layer_by_layer_calls(qt, dtype, mode, val):
+    # inside a stack the last kernel of a decode-sized layer also writes the next layer's router scores; a loop of
+    # single-layer calls scores every layer with the router kernel.  Hidden states, scores and selections of both must
+    # be bit-identical (40 tokens in 5 sequences, one of them empty, 3 layers; also with the score outputs left out)
+    import dataclasses
+    shape = dataclasses.replace(si.C1, act_dtype=dtype)
+    L, T = 3, 40
+    layers_t = [si.layer_tensors(shape, l, 31, unit_gains=False, std=0.06) for l in range(L)]
+    lws = [qt.quantize_layer(t, shape.bits, shape.group) for t in layers_t]
+    cfg = qt.cfg_from_shape(shape)
+    x = si.hidden_states(shape, T, 31)
+    offs, pos = si.ragged_sequences([12, 0, 9, 18, 1], [5, 0, 0, 40, 7])
+    offs, pos = offs.cuda(), pos.cuda()
+    ctx = qt.Context()
+    (qt.qtale_set_exec_ratio if mode == "ratio" else qt.qtale_set_threshold)(ctx, val)
+    xa = x.cuda()
+    za = torch.empty((L, T), dtype=torch.float32, device="cuda")
+    ia = torch.full((L, T), -1, dtype=torch.int32, device="cuda")
+    ca = torch.zeros(L, dtype=torch.int32, device="cuda")
+    qt.qtale_stack_forward(ctx, qt.Stack(cfg, lws), xa, offs, pos, sel_idx=ia, sel_count=ca, scores=za)
+    xb = x.cuda()
+    zb, ib, cb = torch.empty_like(za), torch.full_like(ia, -1), torch.zeros_like(ca)
+    for l in range(L):
+        qt.qtale_layer_forward(ctx, cfg, lws[l], xb, offs, pos, sel_idx=ib[l], sel_count=cb[l:l + 1], scores=zb[l])
+    xc = x.cuda()
+    qt.qtale_stack_forward(ctx, qt.Stack(cfg, lws), xc, offs, pos)          # scores kept in the workspace
+    torch.cuda.synchronize()
+    assert torch.equal(za.view(torch.int32), zb.view(torch.int32))
+    assert torch.equal(ia, ib) and torch.equal(ca, cb)
+    assert torch.equal(xa, xb) and torch.equal(xa, xc)
+    assert int(ca.min().item()) > 0
+
+
 def test_mixed_two_and_four_bit_stack_teacher_forced(qt):
     # interleaved 2-bit / 4-bit layers (the mixed-precision variant of the paper's appendix): every layer carries
     # its own code width, the stack call is the same
